@@ -1,0 +1,196 @@
+/*
+ * ds_attn.h -- C ABI of libdsattn: Double Sparsity decode attention on gfx950.
+ *
+ * The decode step of "Post-Training Sparse Attention with Double Sparsity"
+ * (Algorithm 1): for every (batch, KV head) unit
+ *   1. gather the r calibrated channels of the query and score every cached
+ *      token against the label cache (the same r channels of K),
+ *   2. keep the k best-scoring tokens,
+ *   3. gather those k full K and V rows,
+ *   4. run exact softmax attention over them.
+ *
+ * General conventions
+ *   - fp16 means IEEE binary16 stored as 2 bytes; all arithmetic accumulates in
+ *     binary32.  d (head dimension) must be 128.
+ *   - A "unit" is one (batch b, KV head h); query head hq uses KV head hq / G,
+ *     G = Hq / Hkv (G = 1 is multi-head attention, G > 1 grouped-query).
+ *   - Layouts are dense row-major:
+ *       q        [B, Hq, d]           fp16
+ *       K, V     [B, Hkv, L_max, d]   fp16   one token = one 256-byte row
+ *       label    [B, Hkv, L_max, r]   fp16
+ *       channels [Hkv, r]             int32  distinct, in [0, d); shared over batch
+ *       out      [B, Hq, d]           fp32
+ *       idx      [B, Hkv, k]          int32
+ *     Tokens [0, L) are valid; L_max is the allocated token count (row stride).
+ *   - Ownership: the caller owns every buffer.  The library allocates and frees
+ *     no device memory and keeps no pointer after a call returns.  Scratch comes
+ *     from a caller-provided workspace of ds_workspace_bytes() bytes whose
+ *     contents are undefined between calls; two calls that overlap in time must
+ *     not share a workspace.
+ *   - Device entry points only enqueue work on `stream` (a hipStream_t passed
+ *     as void*, NULL = the null stream) and return without synchronising.
+ *     DS_OK means "validated and enqueued".
+ *   - Errors: every entry point returns a ds_status_t and never throws or
+ *     aborts.  On any error nothing is enqueued and no output is touched.
+ *     NULL required pointer -> DS_ERR_NULL.  d != 128, Hq % Hkv != 0,
+ *     r outside [1, d], k < 1, L < 1, L > L_max, B/Hq/Hkv < 1 -> DS_ERR_SHAPE.
+ *     Misaligned base pointer -> DS_ERR_ALIGN (K, V: 256 bytes; label, q, out,
+ *     idx, workspace: 16 bytes).  Workspace too small -> DS_ERR_WORKSPACE.
+ *     A failed launch -> DS_ERR_HIP.  k > L is not an error: k_eff = min(k, L).
+ *   - Inputs must be finite; behaviour on NaN/Inf is unspecified.
+ *   - Results are bit-identical from run to run for the same inputs and shape.
+ */
+#ifndef DS_ATTN_H
+#define DS_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DS_OK = 0,
+    DS_ERR_NULL = -1,
+    DS_ERR_SHAPE = -2,
+    DS_ERR_ALIGN = -3,
+    DS_ERR_WORKSPACE = -4,
+    DS_ERR_UNSUPPORTED = -5,
+    DS_ERR_HIP = -6
+} ds_status_t;
+
+/* Which statistic ranks the channels (the q / k / qk outlier variants of the
+ * paper's outlier-type ablation, Table 3). */
+typedef enum { DS_CALIB_Q = 0, DS_CALIB_K = 1, DS_CALIB_QK = 2 } ds_calib_mode_t;
+
+typedef struct {
+    int32_t B, Hq, Hkv, d; /* batch, query heads, KV heads, head dim (=128)      */
+    int32_t L, L_max;      /* valid tokens, allocated tokens                      */
+    int32_t r, k;          /* label channels (alpha*d), selected tokens (beta*S)  */
+} ds_shape_t;
+
+/* Static string for a status code (never NULL). */
+const char *ds_strerror(ds_status_t status);
+/* Library version, major*10000 + minor*100 + patch. */
+int ds_version(void);
+
+/*
+ * Offline calibration (Sec. 4.1).  HOST pointers, synchronous, CPU only.
+ * The attention logit is a sum over channels, A = sum_c q_c k_c; the channels
+ * whose terms are largest in magnitude over a calibration set are kept.
+ *   q_calib [N, Hq, d] fp16, k_calib [N, Hkv, d] fp16 : N sample rows.
+ *   mode Q : importance(h, c) = mean over samples and the group's query heads of |q_c|
+ *   mode K : importance(h, c) = mean over samples of |k_c|
+ *   mode QK: product of the two (= mean |q_c k_c| over all query/key pairs).
+ *   channels_out [Hkv, r]: the r most important channels of each KV head in
+ *   ascending channel order; equal importance keeps the lower channel.
+ * Errors: DS_ERR_NULL, DS_ERR_SHAPE (N < 1, r outside [1, d], d < 1,
+ * Hq % Hkv != 0, bad mode).  d is not restricted to 128 here.
+ */
+ds_status_t ds_calibrate_channels(const uint16_t *q_calib, const uint16_t *k_calib,
+                                  int32_t N, int32_t Hq, int32_t Hkv, int32_t d,
+                                  int32_t r, ds_calib_mode_t mode,
+                                  int32_t *channels_out);
+
+/*
+ * Label cache maintenance (Sec. 4.2).  DEVICE pointers.
+ *   label[b, h, t, j] = K[b, h, t, channels[h, j]]   (bit copy)
+ * ds_build_label writes tokens [0, L) (prefill); ds_append_label writes tokens
+ * [t0, t0 + n_new) (decode: call it after the new token's K row is in the cache
+ * and before ds_sparse_decode; L then counts the new token).
+ * Uses shape->{B, Hkv, d, L, L_max, r}; ds_append_label ignores L and needs
+ * 0 <= t0, n_new >= 0, t0 + n_new <= L_max (else DS_ERR_SHAPE).
+ */
+ds_status_t ds_build_label(const void *K, const int32_t *channels, void *label,
+                           const ds_shape_t *shape, void *stream);
+ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
+                            const ds_shape_t *shape, int32_t t0, int32_t n_new,
+                            void *stream);
+
+/* Bytes of workspace any decode/select/attend call with this shape needs.
+ * Pure host function; 0 if the shape is invalid. */
+size_t ds_workspace_bytes(const ds_shape_t *shape);
+
+/*
+ * Double Sparsity decode (Algorithm 1), all four steps.  DEVICE pointers.
+ *   s_hat[t] = sum_{g in group} sum_j q_g[channels[j]] * label[t, j]   (no scale)
+ *   I        = the k_eff tokens with the largest s_hat; equal scores keep the
+ *              lower token index (-0 and +0 are equal)
+ *   out[hq]  = softmax(q_hq . K[I,:]^T / sqrt(d)) . V[I,:]   for each head of the group
+ * The selection is taken on binary32 scores accumulated as fma over j ascending
+ * from 0, with the group's label queries summed first (g ascending).
+ * idx_out may be NULL; otherwise it receives I in ascending token order in
+ * idx_out[b, h, 0 .. k_eff) and -1 in [k_eff, k).
+ */
+ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K,
+                             const void *V, const int32_t *channels, float *out,
+                             int32_t *idx_out, void *workspace,
+                             size_t workspace_bytes, const ds_shape_t *shape,
+                             void *stream);
+
+/*
+ * Dense decode attention over all L tokens (Sec. 2.1), the in-library
+ * comparison point:  out[hq] = softmax(q_hq . K^T / sqrt(d)) . V.
+ * Uses shape->{B, Hq, Hkv, d, L, L_max}; r and k are ignored.
+ */
+ds_status_t ds_dense_decode(const void *q, const void *K, const void *V, float *out,
+                            void *workspace, size_t workspace_bytes,
+                            const ds_shape_t *shape, void *stream);
+
+/*
+ * Split entry points for the offload arrangement (Sec. 5.1: label cache on the
+ * GPU, full K/V in host memory, only the selected rows fetched).
+ * ds_select      = steps 1-2 of Algorithm 1; idx_out (required) as above.
+ * ds_gather_rows_host copies the selected rows: K_host, V_host are pinned host
+ *                  buffers [B, Hkv, L_max, d] addressable from the device;
+ *                  KV_rows (device) is [B, Hkv, k, 2, d]: row i holds K[idx[i]]
+ *                  then V[idx[i]].  Rows with idx < 0 are zero-filled.
+ * ds_attend_rows = steps 4-5 over gathered rows; n_rows_per_unit = k_eff is
+ *                  taken from shape (min(k, L)).
+ */
+ds_status_t ds_select(const void *q, const void *label, const int32_t *channels,
+                      int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                      const ds_shape_t *shape, void *stream);
+ds_status_t ds_gather_rows_host(const void *K_host, const void *V_host,
+                                const int32_t *idx, void *KV_rows,
+                                const ds_shape_t *shape, void *stream);
+ds_status_t ds_attend_rows(const void *q, const void *KV_rows, float *out,
+                           void *workspace, size_t workspace_bytes,
+                           const ds_shape_t *shape, void *stream);
+
+/*
+ * Measurement aids (not part of the method).
+ * ds_probe_stream_read: one pass of plain 16-byte loads over `bytes` bytes of
+ *   device memory (bytes % 16 == 0), xor-folded into sink[0..1023] (uint32,
+ *   device) so the loads cannot be dropped: the read-bandwidth ceiling of the
+ *   device as seen by a kernel of this library.
+ * Per-kernel timing: while enabled, every kernel the library launches is
+ *   bracketed by HIP events on its stream.  ds_profile_read synchronises the
+ *   recorded events of kernel `id` and returns their summed duration and count
+ *   since the last reset.  ids run from 0 to ds_profile_kernel_count() - 1.
+ *   Enabling it perturbs end-to-end timing; leave it off when timing whole calls.
+ */
+ds_status_t ds_probe_stream_read(const void *src, size_t bytes, uint32_t *sink,
+                                 void *stream);
+int ds_profile_kernel_count(void);
+const char *ds_profile_kernel_name(int id);
+ds_status_t ds_profile_enable(int on);
+ds_status_t ds_profile_reset(void);
+ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
+
+/*
+ * Launch-shape knobs, for sweeps (defaults are chosen from the shape):
+ *   knob 0: tokens per workgroup in the scoring kernel   (0 = automatic)
+ *   knob 1: tokens per workgroup in select/attend        (0 = automatic)
+ *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic)
+ * Values must be 0 or a multiple of 1024 ... see ds_tune_set's return code:
+ * DS_ERR_SHAPE for a value the kernels cannot run with.  Process-wide.
+ */
+ds_status_t ds_tune_set(int knob, int value);
+int ds_tune_get(int knob);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DS_ATTN_H */

@@ -1,0 +1,416 @@
+// C-ABI layer of libdsattn: argument validation, launch plans / workspace
+// layout, the host-side offline calibration and the per-kernel event timing.
+// No kernel code lives here; every device step is enqueued through the
+// launchers declared in ds_internal.h.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "ds_internal.h"
+
+namespace ds {
+
+// ---------------------------------------------------------------- knobs
+static int g_tune[3] = {0, 0, 0};
+int tune_get(int knob) { return (knob >= 0 && knob < 3) ? g_tune[knob] : 0; }
+
+// ---------------------------------------------------------------- plans
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static bool shape_ok(const ds_shape_t &s, bool need_rk)
+{
+    if (s.B < 1 || s.Hq < 1 || s.Hkv < 1 || s.d != kD) return false;
+    if (s.Hq % s.Hkv != 0) return false;
+    if (s.L < 1 || s.L > s.L_max) return false;
+    if (need_rk && (s.r < 1 || s.r > s.d || s.k < 1)) return false;
+    if ((int64_t)s.B * s.Hkv > 65535) return false;  // units ride on gridDim.y
+    return true;
+}
+
+bool make_plan(const ds_shape_t &s, Plan *p)
+{
+    if (!shape_ok(s, true)) return false;
+    p->units = s.B * s.Hkv;
+    p->G = s.Hq / s.Hkv;
+    p->k_eff = std::min(s.k, s.L);
+    const int64_t tokens = (int64_t)p->units * s.L;
+
+    int sc = g_tune[0];
+    if (sc == 0) sc = (tokens >= (1 << 20)) ? 2048 : 1024;
+    p->sc_chunk = sc;
+    p->n_sc = (s.L + sc - 1) / sc;
+
+    int ch = g_tune[1];
+    if (ch == 0) {
+        ch = (tokens >= (1 << 21)) ? 1024 : (tokens >= (1 << 20)) ? 512 : 256;
+        while ((s.L + ch - 1) / ch > kMaxChunks && ch < 4096) ch *= 2;
+    }
+    p->ch = ch;
+    p->n_ch = (s.L + ch - 1) / ch;
+    if (p->n_ch > kMaxChunks) return false;
+    p->key_stride = (s.L + 3) & ~3;
+
+    size_t off = 0;
+    p->off_ctl = off;   off = align_up(off + (size_t)p->units * sizeof(UnitCtl), 256);
+    p->off_hist = off;  off = align_up(off + (size_t)p->units * kHistBins * 4, 256);
+    p->off_keys = off;  off = align_up(off + (size_t)p->units * p->key_stride * 4, 256);
+    p->off_cand = off;  off = align_up(off + (size_t)p->units * s.L * 8, 256);
+    p->off_ndef = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
+    p->off_offs = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
+    p->off_part = off;  off = align_up(off + (size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
+    p->total = off;
+    return true;
+}
+
+bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
+{
+    if (!shape_ok(s, false) || n_tokens < 1) return false;
+    p->units = s.B * s.Hkv;
+    p->G = s.Hq / s.Hkv;
+    int ch = g_tune[2];
+    if (ch == 0) {
+        const int64_t tokens = (int64_t)p->units * n_tokens;
+        ch = (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 256 : 64;
+    }
+    p->ch = ch;
+    p->n_ch = (n_tokens + ch - 1) / ch;
+    p->off_part = 0;
+    p->total = align_up((size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
+    return true;
+}
+
+// ---------------------------------------------------------------- per-kernel event timing
+static const char *const kKernelNames[KID_COUNT] = {
+    "k_zero", "k_score", "k_thresh", "k_cand", "k_refine", "k_attend", "k_compact",
+    "k_merge", "k_dense", "k_attend_rows", "k_label", "k_gather_host", "k_probe"};
+
+struct ProfRec { int id; hipEvent_t a, b; };
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_recs;
+static std::vector<hipEvent_t> g_prof_pool;
+static hipEvent_t g_prof_open = nullptr;
+
+static hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(int id, hipStream_t st)
+{
+    (void)id;
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_open = prof_event();
+    if (g_prof_open) (void)hipEventRecord(g_prof_open, st);
+}
+
+void prof_end(int id, hipStream_t st)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_prof_open) return;
+    hipEvent_t e = prof_event();
+    if (!e) { g_prof_pool.push_back(g_prof_open); g_prof_open = nullptr; return; }
+    (void)hipEventRecord(e, st);
+    g_prof_recs.push_back({id, g_prof_open, e});
+    g_prof_open = nullptr;
+}
+
+}  // namespace ds
+
+using namespace ds;
+
+// ---------------------------------------------------------------- helpers
+static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+#define DS_TRY(expr)                                  \
+    do {                                              \
+        if ((expr) != hipSuccess) return DS_ERR_HIP;  \
+    } while (0)
+
+extern "C" {
+
+const char *ds_strerror(ds_status_t status)
+{
+    switch (status) {
+    case DS_OK: return "ok";
+    case DS_ERR_NULL: return "required pointer is NULL";
+    case DS_ERR_SHAPE: return "invalid shape or size argument";
+    case DS_ERR_ALIGN: return "pointer is not sufficiently aligned";
+    case DS_ERR_WORKSPACE: return "workspace is too small";
+    case DS_ERR_UNSUPPORTED: return "configuration not supported";
+    case DS_ERR_HIP: return "HIP runtime reported an error";
+    }
+    return "unknown status";
+}
+
+int ds_version(void) { return 100; }
+
+ds_status_t ds_calibrate_channels(const uint16_t *q_calib, const uint16_t *k_calib, int32_t N,
+                                  int32_t Hq, int32_t Hkv, int32_t d, int32_t r,
+                                  ds_calib_mode_t mode, int32_t *channels_out)
+{
+    if (!q_calib || !k_calib || !channels_out) return DS_ERR_NULL;
+    if (N < 1 || Hq < 1 || Hkv < 1 || d < 1 || r < 1 || r > d || Hq % Hkv != 0) return DS_ERR_SHAPE;
+    if (mode != DS_CALIB_Q && mode != DS_CALIB_K && mode != DS_CALIB_QK) return DS_ERR_SHAPE;
+    const int G = Hq / Hkv;
+    // |x| of a binary16 bit pattern, widened through binary32 bit assembly
+    auto habs = [](uint16_t h) -> double {
+        const uint32_t e = (h >> 10) & 0x1f, m = h & 0x3ff;
+        if (e == 0) return std::ldexp((double)m, -24);
+        if (e == 31) return m ? NAN : INFINITY;
+        return std::ldexp((double)(m | 0x400), (int)e - 25);
+    };
+    std::vector<double> mq(d), mk(d), w(d);
+    std::vector<int32_t> order(d);
+    for (int h = 0; h < Hkv; ++h) {
+        std::fill(mq.begin(), mq.end(), 0.0);
+        std::fill(mk.begin(), mk.end(), 0.0);
+        for (int n = 0; n < N; ++n) {
+            for (int g = 0; g < G; ++g) {
+                const uint16_t *row = q_calib + ((size_t)n * Hq + (size_t)h * G + g) * d;
+                for (int c = 0; c < d; ++c) mq[c] += habs(row[c]);
+            }
+            const uint16_t *krow = k_calib + ((size_t)n * Hkv + h) * d;
+            for (int c = 0; c < d; ++c) mk[c] += habs(krow[c]);
+        }
+        for (int c = 0; c < d; ++c) {
+            const double a = mq[c] / ((double)N * G), b = mk[c] / (double)N;
+            w[c] = mode == DS_CALIB_Q ? a : mode == DS_CALIB_K ? b : a * b;
+            order[c] = c;
+        }
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return w[x] > w[y]; });
+        std::sort(order.begin(), order.begin() + r);
+        std::copy(order.begin(), order.begin() + r, channels_out + (size_t)h * r);
+    }
+    return DS_OK;
+}
+
+static ds_status_t check_label_args(const void *K, const int32_t *channels, void *label,
+                                    const ds_shape_t *s)
+{
+    if (!K || !channels || !label || !s) return DS_ERR_NULL;
+    if (s->B < 1 || s->Hkv < 1 || s->d != kD || s->r < 1 || s->r > s->d || s->L_max < 1)
+        return DS_ERR_SHAPE;
+    if ((int64_t)s->B * s->Hkv > 65535) return DS_ERR_SHAPE;
+    if (!aligned(K, 256) || !aligned(label, 16)) return DS_ERR_ALIGN;
+    return DS_OK;
+}
+
+ds_status_t ds_build_label(const void *K, const int32_t *channels, void *label,
+                           const ds_shape_t *shape, void *stream)
+{
+    ds_status_t st = check_label_args(K, channels, label, shape);
+    if (st != DS_OK) return st;
+    if (shape->L < 1 || shape->L > shape->L_max) return DS_ERR_SHAPE;
+    DS_TRY(launch_label(K, channels, label, *shape, 0, shape->L, (hipStream_t)stream));
+    return DS_OK;
+}
+
+ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
+                            const ds_shape_t *shape, int32_t t0, int32_t n_new, void *stream)
+{
+    ds_status_t st = check_label_args(K, channels, label, shape);
+    if (st != DS_OK) return st;
+    if (t0 < 0 || n_new < 0 || (int64_t)t0 + n_new > shape->L_max) return DS_ERR_SHAPE;
+    DS_TRY(launch_label(K, channels, label, *shape, t0, n_new, (hipStream_t)stream));
+    return DS_OK;
+}
+
+size_t ds_workspace_bytes(const ds_shape_t *shape)
+{
+    if (!shape) return 0;
+    Plan p;
+    DensePlan dp, rp;
+    size_t need = 0;
+    if (make_plan(*shape, &p)) {
+        need = std::max(need, p.total);
+        if (make_dense_plan(*shape, p.k_eff, &rp)) need = std::max(need, rp.total);
+    }
+    if (make_dense_plan(*shape, shape->L, &dp)) need = std::max(need, dp.total);
+    return need;
+}
+
+static ds_status_t select_common(const void *q, const void *label, const int32_t *channels,
+                                 void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                                 Plan *p)
+{
+    if (!q || !label || !channels || !workspace || !shape) return DS_ERR_NULL;
+    if (!shape_ok(*shape, true)) return DS_ERR_SHAPE;
+    if (!make_plan(*shape, p)) return DS_ERR_UNSUPPORTED;
+    if (!aligned(q, 16) || !aligned(label, 16) || !aligned(workspace, 16)) return DS_ERR_ALIGN;
+    if (workspace_bytes < p->total) return DS_ERR_WORKSPACE;
+    return DS_OK;
+}
+
+static ds_status_t enqueue_select(const void *q, const void *label, const int32_t *channels,
+                                  void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st)
+{
+    DS_TRY(launch_zero(ws, p, st));
+    DS_TRY(launch_score(q, label, channels, ws, p, s, st));
+    DS_TRY(launch_thresh(ws, p, st));
+    DS_TRY(launch_cand(ws, p, s, st));
+    DS_TRY(launch_refine(ws, p, s, st));
+    return DS_OK;
+}
+
+ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, const void *V,
+                             const int32_t *channels, float *out, int32_t *idx_out,
+                             void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                             void *stream)
+{
+    if (!K || !V || !out) return DS_ERR_NULL;
+    Plan p;
+    ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p);
+    if (rc != DS_OK) return rc;
+    if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
+        return DS_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, st);
+    if (rc != DS_OK) return rc;
+    DS_TRY(launch_attend_sparse(q, K, V, workspace, idx_out, p, *shape, st));
+    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    return DS_OK;
+}
+
+ds_status_t ds_select(const void *q, const void *label, const int32_t *channels, int32_t *idx_out,
+                      void *workspace, size_t workspace_bytes, const ds_shape_t *shape, void *stream)
+{
+    if (!idx_out) return DS_ERR_NULL;
+    Plan p;
+    ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p);
+    if (rc != DS_OK) return rc;
+    if (!aligned(idx_out, 16)) return DS_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, st);
+    if (rc != DS_OK) return rc;
+    DS_TRY(launch_compact(workspace, idx_out, p, *shape, st));
+    return DS_OK;
+}
+
+ds_status_t ds_dense_decode(const void *q, const void *K, const void *V, float *out,
+                            void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                            void *stream)
+{
+    if (!q || !K || !V || !out || !workspace || !shape) return DS_ERR_NULL;
+    if (!shape_ok(*shape, false)) return DS_ERR_SHAPE;
+    DensePlan p;
+    if (!make_dense_plan(*shape, shape->L, &p)) return DS_ERR_UNSUPPORTED;
+    if (!aligned(K, 256) || !aligned(V, 256) || !aligned(q, 16) || !aligned(out, 16) ||
+        !aligned(workspace, 16))
+        return DS_ERR_ALIGN;
+    if (workspace_bytes < p.total) return DS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    DS_TRY(launch_attend_dense(q, K, V, workspace, p, *shape, st));
+    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    return DS_OK;
+}
+
+ds_status_t ds_gather_rows_host(const void *K_host, const void *V_host, const int32_t *idx,
+                                void *KV_rows, const ds_shape_t *shape, void *stream)
+{
+    if (!K_host || !V_host || !idx || !KV_rows || !shape) return DS_ERR_NULL;
+    if (!shape_ok(*shape, true)) return DS_ERR_SHAPE;
+    if (!aligned(K_host, 256) || !aligned(V_host, 256) || !aligned(KV_rows, 256) || !aligned(idx, 4))
+        return DS_ERR_ALIGN;
+    DS_TRY(launch_gather_host(K_host, V_host, idx, KV_rows, *shape, (hipStream_t)stream));
+    return DS_OK;
+}
+
+ds_status_t ds_attend_rows(const void *q, const void *KV_rows, float *out, void *workspace,
+                           size_t workspace_bytes, const ds_shape_t *shape, void *stream)
+{
+    if (!q || !KV_rows || !out || !workspace || !shape) return DS_ERR_NULL;
+    if (!shape_ok(*shape, true)) return DS_ERR_SHAPE;
+    const int n_rows = std::min(shape->k, shape->L);
+    DensePlan p;
+    if (!make_dense_plan(*shape, n_rows, &p)) return DS_ERR_UNSUPPORTED;
+    if (!aligned(KV_rows, 256) || !aligned(q, 16) || !aligned(out, 16) || !aligned(workspace, 16))
+        return DS_ERR_ALIGN;
+    if (workspace_bytes < p.total) return DS_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    DS_TRY(launch_attend_rows(q, KV_rows, workspace, p, *shape, n_rows, st));
+    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    return DS_OK;
+}
+
+ds_status_t ds_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink) return DS_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || bytes / 16 / (kWG * 8) > 0x7fffffffull) return DS_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return DS_ERR_ALIGN;
+    DS_TRY(launch_probe(src, bytes, sink, (hipStream_t)stream));
+    return DS_OK;
+}
+
+int ds_profile_kernel_count(void) { return KID_COUNT; }
+
+const char *ds_profile_kernel_name(int id)
+{
+    return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : "";
+}
+
+ds_status_t ds_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+    return DS_OK;
+}
+
+ds_status_t ds_profile_reset(void)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto &r : g_prof_recs) {
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_recs.clear();
+    return DS_OK;
+}
+
+ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) return DS_ERR_NULL;
+    if (id < 0 || id >= KID_COUNT) return DS_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    double tot = 0.0;
+    int64_t n = 0;
+    for (auto &r : g_prof_recs) {
+        if (r.id != id) continue;
+        if (hipEventSynchronize(r.b) != hipSuccess) return DS_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return DS_ERR_HIP;
+        tot += ms;
+        ++n;
+    }
+    *total_ms = tot;
+    *launches = n;
+    return DS_OK;
+}
+
+ds_status_t ds_tune_set(int knob, int value)
+{
+    if (knob < 0 || knob > 2) return DS_ERR_SHAPE;
+    if (value < 0) return DS_ERR_SHAPE;
+    if (value != 0) {
+        if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
+        if (knob == 1 && (value % 256 != 0 || value > 4096)) return DS_ERR_SHAPE;
+        if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
+    }
+    g_tune[knob] = value;
+    return DS_OK;
+}
+
+int ds_tune_get(int knob) { return tune_get(knob); }
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libdsattn.
+// Host-side plan (launch shapes + workspace layout) and the launcher functions
+// each .hip file exports to the C-ABI layer.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ds_attn.h"
+
+namespace ds {
+
+constexpr int kD = 128;          // head dimension the kernels are written for
+constexpr int kWG = 256;         // threads per workgroup (4 wavefronts of 64)
+constexpr int kHistBits = 12;    // first-level radix: top 12 bits of the ordered key
+constexpr int kHistBins = 1 << kHistBits;
+constexpr int kKeyShift = 32 - kHistBits;
+constexpr int kPartStride = 132; // floats per attention partial: m, l, 2 pad, acc[128]
+constexpr int kMaxChunks = 8192; // chunk offsets of one unit must fit one workgroup's LDS
+
+// Per-unit selection state in the workspace (64 bytes).
+struct UnitCtl {
+    uint32_t bstar;   // first-level bin holding the k-th largest key
+    uint32_t krem;    // how many keys of that bin are selected (>= 1)
+    uint32_t ncand;   // candidates appended so far (keys in bin bstar)
+    uint32_t T;       // exact k-th largest key
+    int32_t tcut;     // keys equal to T are selected iff token <= tcut
+    uint32_t pad[11];
+};
+static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte record");
+
+enum KernelId {
+    KID_ZERO = 0,
+    KID_SCORE,
+    KID_THRESH,
+    KID_CAND,
+    KID_REFINE,
+    KID_ATTEND,
+    KID_COMPACT,
+    KID_MERGE,
+    KID_DENSE,
+    KID_ATTEND_ROWS,
+    KID_LABEL,
+    KID_GATHER_HOST,
+    KID_PROBE,
+    KID_COUNT
+};
+
+// Launch plan of one sparse decode / select call and its workspace layout.
+struct Plan {
+    int units, G, k_eff;
+    int sc_chunk, n_sc;  // tokens per workgroup / workgroups per unit, scoring
+    int ch, n_ch;        // same for candidate collection, compaction and attention
+    int key_stride;      // uint32 keys per unit (L rounded up to 4)
+    size_t off_ctl, off_hist, off_keys, off_cand, off_ndef, off_offs, off_part;
+    size_t total;
+};
+// Plan of dense / gathered-rows attention (token chunks of dn_chunk).
+struct DensePlan {
+    int units, G;
+    int ch, n_ch;
+    size_t off_part, total;
+};
+
+bool make_plan(const ds_shape_t &s, Plan *p);
+bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);
+
+// profiling hooks (ds_profile.cpp)
+void prof_begin(int id, hipStream_t st);
+void prof_end(int id, hipStream_t st);
+
+// launchers: enqueue only; return the launch error (hipSuccess if fine)
+hipError_t launch_zero(void *ws, const Plan &p, hipStream_t st);
+hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
+                        const Plan &p, const ds_shape_t &s, hipStream_t st);
+hipError_t launch_thresh(void *ws, const Plan &p, hipStream_t st);
+hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st);
+hipError_t launch_refine(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st);
+hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,
+                          hipStream_t st);
+hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws,
+                                int32_t *idx_out, const Plan &p, const ds_shape_t &s,
+                                hipStream_t st);
+hipError_t launch_merge(const void *part, int n_ch, float *out, int n_heads, hipStream_t st);
+hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws,
+                               const DensePlan &p, const ds_shape_t &s, hipStream_t st);
+hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, const DensePlan &p,
+                              const ds_shape_t &s, int n_rows, hipStream_t st);
+hipError_t launch_label(const void *K, const int32_t *channels, void *label, const ds_shape_t &s,
+                        int t0, int n, hipStream_t st);
+hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,
+                              const ds_shape_t &s, hipStream_t st);
+hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
+
+int tune_get(int knob);
+
+}  // namespace ds

@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on seeded synthetic inputs.  Small/odd shapes span several tiles
+and ragged tails; the BASELINE configurations run at full size in the launch
+configuration the bench times."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_07092_amd as ds
+from oracle import ds_oracle as O
+from tests.parity_util import Case, check_index_structure, check_output, full_parity, to_dev
+from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_numpy, make_layer_torch,
+                       outlier_channels)
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_channels(Hkv, d, r, seed, sort=True):
+    rng = np.random.default_rng(seed)
+    rows = [rng.permutation(d)[:r] for _ in range(Hkv)]
+    return np.stack([np.sort(x) if sort else x for x in rows]).astype(np.int32)
+
+
+def small_workload(B, Hq, Hkv, L, r, k):
+    return Workload("t", B, Hq, Hkv, 128, L, r, k, 1)
+
+
+# ---------------------------------------------------------------- odd shapes
+@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", [
+    (1, 1, 1, 1, 1, 8, 1),            # single token
+    (1, 2, 2, 5, 8, 8, 3),
+    (2, 4, 4, 63, 64, 8, 7),
+    (1, 3, 3, 257, 300, 16, 16),
+    (2, 2, 2, 1000, 1000, 8, 62),     # ragged chunk tail
+    (1, 4, 4, 4097, 4100, 8, 256),    # one token past a tile
+    (1, 2, 2, 2048, 2048, 8, 2048),   # k = L
+    (1, 2, 2, 300, 512, 8, 999),      # k > L clamps
+    (1, 2, 2, 3000, 3000, 8, 1),      # k = 1
+    (1, 2, 2, 1500, 1500, 1, 100),    # r = 1 (scalar label path)
+    (1, 2, 2, 1500, 1500, 3, 100),    # odd r
+    (1, 2, 2, 1500, 1500, 24, 100),   # r % 8 == 0, generic vector path
+    (1, 1, 1, 700, 700, 128, 50),     # r = d
+    (3, 8, 2, 900, 1024, 8, 57),      # GQA group 4
+    (2, 16, 2, 777, 800, 8, 40),      # GQA group 8
+    (1, 6, 2, 520, 520, 16, 33),      # GQA group 3 (no power-of-two tile)
+    (1, 32, 2, 400, 400, 8, 25),      # GQA group 16 (two passes of 8)
+])
+def test_small_shapes(B, Hq, Hkv, L, L_max, r, k):
+    w = small_workload(B, Hq, Hkv, L, r, k)
+    t = make_layer_numpy(w, layer=L % 7, L_max=L_max)
+    ch = rand_channels(Hkv, 128, r, seed=L + r, sort=(r != 3))
+    case = Case(t["q"], t["K"], t["V"], ch, L, k)
+    full_parity(case, what=f"B{B} Hq{Hq} Hkv{Hkv} L{L} r{r} k{k}")
+
+
+def test_identity_channels_k_eq_L_is_dense():
+    w = small_workload(1, 2, 2, 640, 128, 640)
+    t = make_layer_numpy(w)
+    ch = np.tile(np.arange(128, dtype=np.int32), (2, 1))
+    case = Case(t["q"], t["K"], t["V"], ch, 640, 640)
+    lab = case.gpu_build_label()
+    assert np.array_equal(lab.view(np.uint16), t["K"].view(np.uint16))
+    out, idx = case.gpu_sparse()
+    assert (idx == np.arange(640)).all()
+    check_output(out, O.dense_decode(t["q"], t["K"], t["V"], 640), "k=L vs dense oracle")
+    check_output(case.gpu_dense(), O.dense_decode(t["q"], t["K"], t["V"], 640), "dense")
+
+
+# ---------------------------------------------------------------- ties
+@pytest.mark.parametrize("L,k,G", [(1200, 100, 1), (5000, 313, 1), (2500, 77, 4)])
+def test_integer_scores_many_exact_ties(L, k, G):
+    """Small-integer q and K make thousands of equal scores: the lowest token
+    indices must win, exactly as in the oracle's full sort."""
+    rng = np.random.default_rng(L)
+    Hkv = 2
+    q = rng.integers(-2, 3, size=(1, Hkv * G, 128)).astype(np.float16)
+    K = rng.integers(-2, 3, size=(1, Hkv, L, 128)).astype(np.float16)
+    V = rng.standard_normal((1, Hkv, L, 128)).astype(np.float16)
+    ch = rand_channels(Hkv, 128, 8, seed=1)
+    case = Case(q, K, V, ch, L, k)
+    full_parity(case, check_dense=False, what="ties")
+
+
+def test_all_scores_equal_selects_first_k_tokens():
+    L, k = 3000, 129
+    q = np.zeros((1, 2, 128), np.float16)                  # every approximate score is +0
+    rng = np.random.default_rng(0)
+    K = rng.standard_normal((1, 2, L, 128)).astype(np.float16)
+    K[0, 1] = -np.abs(K[0, 1])                             # and -0 * x products stay zero
+    V = rng.standard_normal((1, 2, L, 128)).astype(np.float16)
+    case = Case(q, K, V, rand_channels(2, 128, 8, 3), L, k)
+    case.gpu_build_label()
+    out, idx = case.gpu_sparse()
+    assert (idx == np.arange(k)).all()
+    full_parity(case, check_dense=False, what="all equal")
+
+
+def test_negative_zero_ties_with_positive_zero():
+    L, k = 600, 10
+    q = np.zeros((1, 1, 128), np.float16); q[0, 0, 5] = -1.0
+    K = np.zeros((1, 1, L, 128), np.float16)               # scores are -1 * (+0) = -0 and -1 * (-0) = +0
+    K[0, 0, ::2, 5] = -0.0
+    K[0, 0, 300:, 5] = 1.0                                 # clearly lower scores (-1)
+    V = np.random.default_rng(1).standard_normal((1, 1, L, 128)).astype(np.float16)
+    ch = np.array([[5, 6, 7, 8, 9, 10, 11, 12]], np.int32)
+    case = Case(q, K, V, ch, L, k)
+    case.gpu_build_label()
+    _, idx = case.gpu_sparse()
+    assert idx[0, 0].tolist() == list(range(10))
+    full_parity(case, check_dense=False, what="signed zeros")
+
+
+# ---------------------------------------------------------------- label cache
+def test_append_label_equals_build_and_error_codes():
+    w = small_workload(2, 4, 4, 500, 8, 10)
+    t = make_layer_numpy(w, L_max=512)
+    ch = rand_channels(4, 128, 8, 9)
+    case = Case(t["q"], t["K"], t["V"], ch, 500, 10)
+    full = case.gpu_build_label().copy()
+    case.label.zero_()
+    shp = ds.shape(2, 4, 4, 128, 490, 512, 8, 10)
+    ds.ds_build_label(case.K, case.ch, case.label, shp)
+    ds.ds_append_label(case.K, case.ch, case.label, shp, 490, 1)      # one decode step
+    ds.ds_append_label(case.K, case.ch, case.label, shp, 491, 9)      # a burst
+    ds.ds_append_label(case.K, case.ch, case.label, shp, 500, 0)      # nothing
+    torch.cuda.synchronize()
+    assert np.array_equal(case.label.cpu().numpy().view(np.uint16), full.view(np.uint16))
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_append_label(case.K, case.ch, case.label, shp, 510, 3)
+    assert e.value.status == ds.DS_ERR_SHAPE
+
+
+def test_device_entry_points_reject_bad_arguments_without_touching_outputs():
+    w = small_workload(1, 2, 2, 300, 8, 16)
+    t = make_layer_numpy(w)
+    case = Case(t["q"], t["K"], t["V"], rand_channels(2, 128, 8, 4), 300, 16)
+    case.gpu_build_label()
+    out = torch.full((1, 2, 128), 5.0, dtype=torch.float32, device="cuda")
+    small_ws = torch.empty(64, dtype=torch.uint8, device="cuda")
+    cases = [
+        (lambda: ds.ds_sparse_decode(case.q, case.label, case.K, case.V, case.ch, out, None, small_ws, case.shape),
+         ds.DS_ERR_WORKSPACE),
+        (lambda: ds.ds_sparse_decode(case.q, case.label, None, case.V, case.ch, out, None, case.ws, case.shape),
+         ds.DS_ERR_NULL),
+        (lambda: ds.ds_sparse_decode(case.q, case.label, case.K, case.V, case.ch, out, None, case.ws,
+                                     ds.shape(1, 2, 2, 64, 300, 300, 8, 16)), ds.DS_ERR_SHAPE),
+        (lambda: ds.ds_sparse_decode(case.q, case.label, case.K, case.V, case.ch, out, None, case.ws,
+                                     ds.shape(1, 2, 2, 128, 301, 300, 8, 16)), ds.DS_ERR_SHAPE),
+        (lambda: ds.ds_sparse_decode(case.q, case.label, case.K.view(-1)[8:].view(-1), case.V, case.ch, out, None,
+                                     case.ws, case.shape), ds.DS_ERR_ALIGN),
+        (lambda: ds.ds_dense_decode(case.q, case.K, case.V, out, small_ws, case.shape), ds.DS_ERR_WORKSPACE),
+        (lambda: ds.ds_select(case.q, case.label, case.ch, None, case.ws, case.shape), ds.DS_ERR_NULL),
+    ]
+    for fn, want in cases:
+        with pytest.raises(ds.DsError) as e:
+            fn()
+        assert e.value.status == want
+    torch.cuda.synchronize()
+    assert (out == 5.0).all()
+
+
+# ---------------------------------------------------------------- offload split path
+def test_select_gather_from_pinned_host_attend_rows():
+    w = small_workload(1, 4, 4, 3000, 8, 200)
+    t = make_layer_numpy(w)
+    ch = rand_channels(4, 128, 8, 12)
+    case = Case(t["q"], t["K"], t["V"], ch, 3000, 200)
+    lab_ref = case.oracle_label()
+    case.gpu_build_label()
+    Kp = torch.from_numpy(t["K"]).pin_memory()
+    Vp = torch.from_numpy(t["V"]).pin_memory()
+    idx = torch.full((1, 4, 200), -7, dtype=torch.int32, device="cuda")
+    rows = torch.empty((1, 4, 200, 2, 128), dtype=torch.float16, device="cuda")
+    out = torch.zeros((1, 4, 128), dtype=torch.float32, device="cuda")
+    ds.ds_select(case.q, case.label, case.ch, idx, case.ws, case.shape)
+    ds.ds_gather_rows_host(Kp, Vp, idx, rows, case.shape)
+    ds.ds_attend_rows(case.q, rows, out, case.ws, case.shape)
+    torch.cuda.synchronize()
+    idx_h, rows_h = idx.cpu().numpy(), rows.cpu().numpy()
+    ref_out, ref_idx = O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, 3000, 200, precision=32)
+    assert np.array_equal(idx_h, ref_idx)
+    for h in range(4):
+        assert np.array_equal(rows_h[0, h, :, 0].view(np.uint16), t["K"][0, h, idx_h[0, h]].view(np.uint16))
+        assert np.array_equal(rows_h[0, h, :, 1].view(np.uint16), t["V"][0, h, idx_h[0, h]].view(np.uint16))
+    check_output(out.cpu().numpy(), ref_out, "offload split path")
+
+
+# ---------------------------------------------------------------- calibration feeds the path
+def test_calibrated_channels_drive_selection_c1():
+    w = WORKLOADS["C1"]
+    qc, kc = make_calibration_numpy(w)
+    ch = ds.ds_calibrate_channels(qc, kc, w.r, ds.DS_CALIB_QK)
+    assert np.array_equal(ch, outlier_channels(w.Hkv, w.d))
+    assert np.array_equal(ch, O.calibrate(qc, kc, w.r, 2)[0])
+    t = make_layer_numpy(w)
+    case = Case(t["q"], t["K"], t["V"], ch, w.L, w.k)
+    rep = full_parity(case, what="C1")
+    print("C1", rep)
+
+
+# ---------------------------------------------------------------- full-size configurations
+def _full_config(name, check_dense_heads=None):
+    w = WORKLOADS[name]
+    qc, kc = make_calibration_numpy(w)
+    mode = ds.DS_CALIB_QK if w.G == 1 else ds.DS_CALIB_Q
+    ch = ds.ds_calibrate_channels(qc, kc, w.r, mode)
+    t = make_layer_torch(w, "cuda", layer=0)
+    case = Case.from_torch(t, ch, w.L, w.k)
+    rep = full_parity(case, check_dense=False, what=name)
+    # dense: compare a sample of batches (the oracle's dense pass is the slow part)
+    nb = min(w.B, 2)
+    d_gpu = case.gpu_dense()
+    d_ref = O.dense_decode(case.q_h[:nb], case.K_h[:nb], case.V_h[:nb], w.L)
+    rep["dense"] = check_output(d_gpu[:nb], d_ref, name + " dense")
+    print(name, rep)
+
+
+def test_full_config_c2():
+    _full_config("C2")
+
+
+def test_full_config_c3_headline():
+    _full_config("C3")
+
+
+def test_full_config_c4a_gqa8():
+    _full_config("C4a")
+
+
+def test_full_config_c4b_gqa4():
+    _full_config("C4b")
+
+
+def test_full_config_c5_offload_rows_from_pinned_host():
+    """L = 256K, K/V in pinned host memory, label cache on the device: select on
+    the GPU, fetch the k rows over the host link, attend over them."""
+    w = WORKLOADS["C5"]
+    qc, kc = make_calibration_numpy(w)
+    ch = ds.ds_calibrate_channels(qc, kc, w.r, ds.DS_CALIB_QK)
+    t = make_layer_torch(w, "cuda", layer=0, pin_kv=True)
+    Kp, Vp = t["K"], t["V"]
+    K_h, V_h, q_h = Kp.numpy(), Vp.numpy(), t["q"].cpu().numpy()
+    shp = ds.shape(w.B, w.Hq, w.Hkv, w.d, w.L, w.L, w.r, w.k)
+    # the label cache is built from a temporary device copy of K; K then leaves the device
+    label = torch.empty((w.B, w.Hkv, w.L, w.r), dtype=torch.float16, device="cuda")
+    ch_d = to_dev(ch)
+    Kd = Kp.cuda()
+    ds.ds_build_label(Kd, ch_d, label, shp)
+    torch.cuda.synchronize()
+    del Kd
+    torch.cuda.synchronize()
+    lab_ref = O.build_label(K_h, ch, w.L)
+    assert np.array_equal(label.cpu().numpy().view(np.uint16), lab_ref.view(np.uint16))
+    ws = torch.empty(ds.ds_workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.B, w.Hkv, w.k), dtype=torch.int32, device="cuda")
+    rows = torch.empty((w.B, w.Hkv, w.k, 2, w.d), dtype=torch.float16, device="cuda")
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
+    ds.ds_select(t["q"], label, ch_d, idx, ws, shp)
+    ds.ds_gather_rows_host(Kp, Vp, idx, rows, shp)
+    ds.ds_attend_rows(t["q"], rows, out, ws, shp)
+    torch.cuda.synchronize()
+    ref_out, ref_idx = O.sparse_decode(q_h, lab_ref, K_h, V_h, ch, w.L, w.k, precision=32)
+    idx_h = idx.cpu().numpy()
+    check_index_structure(idx_h, w.L, w.k)
+    assert np.array_equal(idx_h, ref_idx)
+    print("C5", check_output(out.cpu().numpy(), ref_out, "C5 offload"))
+
+
+# ---------------------------------------------------------------- determinism across tuning-independent reruns
+def test_run_to_run_bytes_identical_c1_many_times():
+    w = WORKLOADS["C1"]
+    t = make_layer_numpy(w)
+    case = Case(t["q"], t["K"], t["V"], outlier_channels(w.Hkv, w.d), w.L, w.k)
+    case.gpu_build_label()
+    first = None
+    for _ in range(5):
+        out, idx = case.gpu_sparse()
+        blob = out.tobytes() + idx.tobytes()
+        first = first or blob
+        assert blob == first

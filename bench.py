@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Throughput of the Double Sparsity decode-attention hot path on one MI355X.
+
+A step is one decode step of the attention path over every layer of the
+workload: for each layer one ds_sparse_decode call (score -> top-k -> gather ->
+softmax.V) on that layer's own label cache and K/V cache, all resident in HBM
+before the clock starts.  Distinct caches per layer keep consecutive calls from
+re-reading cache-resident data.  Prints one JSON line (see the fields below).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3", help="C1, C2, C3 (headline), C4a, C4b")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = workload's)")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every call from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--tune", default="", help="knob=value,... (ds_tune_set)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path has no cross-GPU step); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2408_07092_amd as ds
+    from workloads import WORKLOADS, make_calibration_numpy, make_layer_torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = WORKLOADS[args.workload]
+    for kv in filter(None, args.tune.split(",")):
+        kn, val = kv.split("=")
+        ds.ds_tune_set(int(kn), int(val))
+
+    # ---- resident caches: as many distinct layers as the workload has (capped by memory)
+    layer_bytes = w.units * w.L * (2 * w.d * 2 + w.r * 2)
+    free, _ = torch.cuda.mem_get_info()
+    n_layers = args.layers or w.n_layers
+    n_layers = max(1, min(n_layers, int(free * 0.8) // layer_bytes))
+    shp = ds.shape(w.B, w.Hq, w.Hkv, w.d, w.L, w.L, w.r, w.k)
+    mode = ds.DS_CALIB_QK if w.G == 1 else ds.DS_CALIB_Q
+    layers = []
+    t_gen = time.time()
+    for l in range(n_layers):
+        qc, kc = make_calibration_numpy(w, layer=l)
+        ch = torch.from_numpy(ds.ds_calibrate_channels(qc, kc, w.r, mode)).to(dev)
+        t = make_layer_torch(w, dev, layer=l)
+        label = torch.empty((w.B, w.Hkv, w.L, w.r), dtype=torch.float16, device=dev)
+        ds.ds_build_label(t["K"], ch, label, shp)
+        layers.append((t["q"], label, t["K"], t["V"], ch))
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    ws = torch.empty(ds.ds_workspace_bytes(shp), dtype=torch.uint8, device=dev)
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+
+    def sparse_sweep():
+        for (q, label, K, V, ch) in layers:
+            ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+
+    def dense_sweep():
+        for (q, label, K, V, ch) in layers:
+            ds.ds_dense_decode(q, K, V, out, ws, shp)
+
+    stream = torch.cuda.Stream(device=dev)
+
+    def timed(fn, steps, warmup, use_graph):
+        """Returns (ms_per_step by wall clock, ms_per_step by events on the launch stream)."""
+        with torch.cuda.stream(stream):
+            runner = fn
+            if use_graph:
+                fn(); stream.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    fn()
+                runner = g.replay
+            for _ in range(warmup):
+                runner()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record(stream)
+            for _ in range(steps):
+                runner()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    use_graph = not args.no_graph
+    ms_step, ms_step_ev = timed(sparse_sweep, args.steps, args.warmup, use_graph)
+    us_layer = ms_step * 1e3 / n_layers
+
+    # ---- per-kernel durations of the same K steps (events bracketing every launch, eager)
+    ds.ds_profile_reset(); ds.ds_profile_enable(True)
+    with torch.cuda.stream(stream):
+        for _ in range(args.steps):
+            sparse_sweep()
+        torch.cuda.synchronize()
+    prof = ds.ds_profile_read()
+    ds.ds_profile_enable(False); ds.ds_profile_reset()
+    kernels_us = {k: round(v[0] * 1e3 / v[1], 3) for k, v in prof.items()}
+    dom = "k_attend"
+    dom_bytes = w.units * w.k * w.d * 2 * 2              # k full K and V rows per unit (Sec. 5.3)
+    dom_us = kernels_us[dom]
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+
+    res = {
+        "metric": "sparse decode attention us/layer at L=%d, 1/%d token sparsity (achieved HBM GB/s in extra)" % (w.L, w.L // w.k),
+        "value": round(us_layer, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "L": w.L,
+                   "r": w.r, "k": w.k, "layers_per_step": n_layers, "hip_graph": use_graph},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
+    }
+    alg = w.algorithmic_bytes()
+    extra = {
+        "algorithmic_bytes_per_layer": alg,
+        "achieved_GBps_whole_path": round(alg / (us_layer * 1e-6) / 1e9, 1),
+        "hbm_frac_whole_path": round(alg / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "us_per_layer_by_stream_events": round(ms_step_ev * 1e3 / n_layers, 3),
+        "attention_tokens_per_s": round(w.B / (w.n_layers * us_layer * 1e-6), 1),
+        "kernels_avg_us": kernels_us,
+        "setup_s": round(t_gen, 1),
+    }
+
+    # ---- in-library dense decode on the same caches
+    if not args.no_dense:
+        d_steps = max(2, args.steps // 4)
+        d_ms, _ = timed(dense_sweep, d_steps, 1, use_graph)
+        d_us = d_ms * 1e3 / n_layers
+        extra["dense_us_per_layer"] = round(d_us, 3)
+        extra["dense_achieved_GBps"] = round(w.dense_bytes() / (d_us * 1e-6) / 1e9, 1)
+        extra["speedup_vs_dense"] = round(d_us / us_layer, 3)
+
+    # ---- measured read ceiling of this device: plain 16-byte loads over one layer's K cache at a time
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+
+    def probe_sweep():
+        for (q, label, K, V, ch) in layers:
+            ds.ds_probe_stream_read(K, sink)
+    p_ms, _ = timed(probe_sweep, max(2, args.steps // 4), 1, use_graph)
+    extra["stream_read_ceiling_GBps"] = round(n_layers * layers[0][2].numel() * 2 / (p_ms * 1e-3) / 1e9, 1)
+
+    # ---- CPU oracle on the host cores, bounded sample
+    if not args.no_cpu:
+        from oracle import ds_oracle as O
+        q, label, K, V, ch = layers[0]
+        qh, Kh, Vh, chh = q.cpu().numpy(), K.cpu().numpy(), V.cpu().numpy(), ch.cpu().numpy()
+        lab_h = O.build_label(Kh, chh, w.L)
+        cores = len(os.sched_getaffinity(0))
+        reps, t_cpu = 0, 0.0
+        while reps < 3 and t_cpu < 20.0:
+            t0 = time.perf_counter()
+            ref_out, _ = O.sparse_decode(qh, lab_h, Kh, Vh, chh, w.L, w.k)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        # the sample doubles as an end-of-run sanity check of the timed path
+        ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+        torch.cuda.synchronize()
+        err = float(np.abs(out.cpu().numpy().astype(np.float64) - ref_out).max())
+        extra["max_abs_err_vs_oracle_layer0"] = err
+        res["cpu_baseline"] = {"value": round(t_cpu / reps * 1e6, 1), "unit": "us/layer", "cores": cores,
+                               "kind": "oracle", "sample": f"layer 0 of {w.name}, all {w.units} units, {reps} repetitions"}
+    res["extra"] = extra
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

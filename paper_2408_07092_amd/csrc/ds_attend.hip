@@ -90,7 +90,8 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
         if (a.idx_out) {
             int32_t *io = a.idx_out + (size_t)u * a.k;
             const uint32_t off = a.offs[(size_t)u * a.n_ch + c];
-            for (int i = tid; i < n; i += kWG) io[off + i] = sel[i];
+            for (int i = tid; i < n; i += kWG)
+                if (off + i < (uint32_t)a.k_eff) io[off + i] = sel[i];
             if (c == 0)
                 for (int i = a.k_eff + tid; i < a.k; i += kWG) io[i] = -1;
         }

@@ -335,7 +335,8 @@ __global__ __launch_bounds__(kWG) void k_compact(const uint32_t *__restrict__ ke
     __syncthreads();
     int32_t *io = idx_out + (size_t)u * k;
     const uint32_t off = offs[(size_t)u * n_ch + c];
-    for (int i = tid; i < n; i += kWG) io[off + i] = sel[i];
+    for (int i = tid; i < n; i += kWG)
+        if (off + i < (uint32_t)k_eff) io[off + i] = sel[i];
     if (c == 0)
         for (int i = k_eff + tid; i < k; i += kWG) io[i] = -1;
 }

@@ -75,7 +75,7 @@ def main():
         layers.append((t["q"], label, t["K"], t["V"], ch))
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
-    ws = torch.empty(ds.ds_workspace_bytes(shp), dtype=torch.uint8, device=dev)
+    ws = ds.ds_workspace_alloc(shp, dev)
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
 
     def sparse_sweep():

@@ -24,9 +24,12 @@
  *     Tokens [0, L) are valid; L_max is the allocated token count (row stride).
  *   - Ownership: the caller owns every buffer.  The library allocates and frees
  *     no device memory and keeps no pointer after a call returns.  Scratch comes
- *     from a caller-provided workspace of ds_workspace_bytes() bytes whose
- *     contents are undefined between calls; two calls that overlap in time must
- *     not share a workspace.
+ *     from a caller-provided workspace of ds_workspace_bytes() bytes.  The
+ *     workspace carries a few counters that every call leaves at zero again, so
+ *     it must be cleared once with ds_workspace_init() after allocation, must
+ *     not be written by the caller, and must be cleared again before it is used
+ *     with a different shape or after a call that returned DS_ERR_HIP.  Two
+ *     calls that overlap in time must not share a workspace.
  *   - Device entry points only enqueue work on `stream` (a hipStream_t passed
  *     as void*, NULL = the null stream) and return without synchronising.
  *     DS_OK means "validated and enqueued".
@@ -108,9 +111,12 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
                             const ds_shape_t *shape, int32_t t0, int32_t n_new,
                             void *stream);
 
-/* Bytes of workspace any decode/select/attend call with this shape needs.
- * Pure host function; 0 if the shape is invalid. */
+/* Bytes of workspace any decode/select/attend call with this shape needs
+ * (a multiple of 256).  Pure host function; 0 if the shape is invalid. */
 size_t ds_workspace_bytes(const ds_shape_t *shape);
+/* Enqueues the clearing of a freshly allocated workspace (all workspace_bytes,
+ * a multiple of 16).  Required once before the first call that uses it. */
+ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Double Sparsity decode (Algorithm 1), all four steps.  DEVICE pointers.
@@ -181,11 +187,12 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
 
 /*
  * Launch-shape knobs, for sweeps (defaults are chosen from the shape):
- *   knob 0: tokens per workgroup in the scoring kernel   (0 = automatic)
- *   knob 1: tokens per workgroup in select/attend        (0 = automatic)
- *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic)
- * Values must be 0 or a multiple of 1024 ... see ds_tune_set's return code:
- * DS_ERR_SHAPE for a value the kernels cannot run with.  Process-wide.
+ *   knob 0: tokens per workgroup in the scoring kernel   (0 = automatic; multiple of 256)
+ *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 256, <= 4096)
+ *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
+ * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
+ * changing a knob changes ds_workspace_bytes() and the workspace layout, so
+ * re-query the size and clear the workspace again afterwards.
  */
 ds_status_t ds_tune_set(int knob, int value);
 int ds_tune_get(int knob);

@@ -22,7 +22,7 @@ DS_CALIB_Q, DS_CALIB_K, DS_CALIB_QK = 0, 1, 2
 
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
-    "ds_workspace_bytes", "ds_sparse_decode", "ds_dense_decode", "ds_select",
+    "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
     "ds_tune_set", "ds_tune_get",
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
         L.ds_append_label.argtypes = [vp, vp, vp, shp, i32, i32, vp]
         L.ds_workspace_bytes.restype = sz
         L.ds_workspace_bytes.argtypes = [shp]
+        L.ds_workspace_init.argtypes = [vp, sz, vp]
         L.ds_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_dense_decode.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_select.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
@@ -137,6 +138,21 @@ def ds_append_label(K, channels, label, shp: DsShape, t0: int, n_new: int, strea
 
 def ds_workspace_bytes(shp: DsShape) -> int:
     return int(lib().ds_workspace_bytes(ctypes.byref(shp)))
+
+
+def ds_workspace_init(workspace, stream=None):
+    _check(lib().ds_workspace_init(_dp(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "ds_workspace_init")
+
+
+def ds_workspace_alloc(shp: DsShape, device="cuda") -> "torch.Tensor":
+    """torch-allocated, cleared workspace for `shp` (convenience of the binding)."""
+    n = ds_workspace_bytes(shp)
+    if n == 0:
+        raise DsError(DS_ERR_SHAPE, "ds_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    ds_workspace_init(ws)
+    return ws
 
 
 def ds_sparse_decode(q, label, K, V, channels, out, idx_out, workspace, shp: DsShape, stream=None):

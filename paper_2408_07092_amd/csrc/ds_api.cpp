@@ -26,6 +26,8 @@ static bool shape_ok(const ds_shape_t &s, bool need_rk)
     if (s.L < 1 || s.L > s.L_max) return false;
     if (need_rk && (s.r < 1 || s.r > s.d || s.k < 1)) return false;
     if ((int64_t)s.B * s.Hkv > 65535) return false;  // units ride on gridDim.y
+    if ((int64_t)s.L_max * kD * 2 > 0xffffffffll) return false;  // rows are addressed by 32-bit byte offsets
+    if (need_rk && (int64_t)std::min(s.k, s.L) * kD * 4 > 0xffffffffll) return false;
     return true;
 }
 
@@ -76,15 +78,20 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
     }
     p->ch = ch;
     p->n_ch = (n_tokens + ch - 1) / ch;
-    p->off_part = 0;
-    p->total = align_up((size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
+    // same control prefix (records + histograms) as the sparse plan, so that sparse and dense
+    // calls may alternate on one workspace without disturbing each other's zeroed counters
+    size_t off = 0;
+    p->off_ctl = off;   off = align_up(off + (size_t)p->units * sizeof(UnitCtl), 256);
+    off = align_up(off + (size_t)p->units * kHistBins * 4, 256);
+    p->off_part = off;  off = align_up(off + (size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
+    p->total = off;
     return true;
 }
 
 // ---------------------------------------------------------------- per-kernel event timing
 static const char *const kKernelNames[KID_COUNT] = {
-    "k_zero", "k_score", "k_thresh", "k_cand", "k_refine", "k_attend", "k_compact",
-    "k_merge", "k_dense", "k_attend_rows", "k_label", "k_gather_host", "k_probe"};
+    "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
+    "k_attend_rows", "k_label", "k_gather_host", "k_probe"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -241,6 +248,15 @@ size_t ds_workspace_bytes(const ds_shape_t *shape)
     return need;
 }
 
+ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return DS_ERR_NULL;
+    if (workspace_bytes == 0 || workspace_bytes % 16 != 0) return DS_ERR_SHAPE;
+    if (!aligned(workspace, 16)) return DS_ERR_ALIGN;
+    DS_TRY(launch_init(workspace, workspace_bytes, (hipStream_t)stream));
+    return DS_OK;
+}
+
 static ds_status_t select_common(const void *q, const void *label, const int32_t *channels,
                                  void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
                                  Plan *p)
@@ -254,13 +270,11 @@ static ds_status_t select_common(const void *q, const void *label, const int32_t
 }
 
 static ds_status_t enqueue_select(const void *q, const void *label, const int32_t *channels,
-                                  void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st)
+                                  void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
+                                  hipStream_t st)
 {
-    DS_TRY(launch_zero(ws, p, st));
     DS_TRY(launch_score(q, label, channels, ws, p, s, st));
-    DS_TRY(launch_thresh(ws, p, st));
-    DS_TRY(launch_cand(ws, p, s, st));
-    DS_TRY(launch_refine(ws, p, s, st));
+    DS_TRY(launch_cand(ws, p, s, want_offsets, st));
     return DS_OK;
 }
 
@@ -276,10 +290,9 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
     if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    rc = enqueue_select(q, label, channels, workspace, p, *shape, st);
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st);
     if (rc != DS_OK) return rc;
-    DS_TRY(launch_attend_sparse(q, K, V, workspace, idx_out, p, *shape, st));
-    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st));
     return DS_OK;
 }
 
@@ -292,7 +305,7 @@ ds_status_t ds_select(const void *q, const void *label, const int32_t *channels,
     if (rc != DS_OK) return rc;
     if (!aligned(idx_out, 16)) return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    rc = enqueue_select(q, label, channels, workspace, p, *shape, st);
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, true, st);
     if (rc != DS_OK) return rc;
     DS_TRY(launch_compact(workspace, idx_out, p, *shape, st));
     return DS_OK;
@@ -311,8 +324,7 @@ ds_status_t ds_dense_decode(const void *q, const void *K, const void *V, float *
         return DS_ERR_ALIGN;
     if (workspace_bytes < p.total) return DS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    DS_TRY(launch_attend_dense(q, K, V, workspace, p, *shape, st));
-    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    DS_TRY(launch_attend_dense(q, K, V, workspace, out, p, *shape, st));
     return DS_OK;
 }
 
@@ -339,8 +351,7 @@ ds_status_t ds_attend_rows(const void *q, const void *KV_rows, float *out, void 
         return DS_ERR_ALIGN;
     if (workspace_bytes < p.total) return DS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    DS_TRY(launch_attend_rows(q, KV_rows, workspace, p, *shape, n_rows, st));
-    DS_TRY(launch_merge(static_cast<char *>(workspace) + p.off_part, p.n_ch, out, p.units * p.G, st));
+    DS_TRY(launch_attend_rows(q, KV_rows, workspace, out, p, *shape, n_rows, st));
     return DS_OK;
 }
 

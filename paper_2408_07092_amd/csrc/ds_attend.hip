@@ -7,12 +7,16 @@
 // rows per instruction -- 16 lanes x 16 bytes cover one row -- so each 16-lane
 // group ("slot") owns a row at a time and keeps its own online-softmax state
 // (running max m, denominator l, 8 output channels per lane).  The 16 slots of
-// a workgroup are merged in a fixed order, then a merge kernel combines the
-// chunks of a head in chunk order, so results are bit-reproducible.
+// a workgroup are merged in a fixed order and written as one partial per chunk;
+// the last workgroup of a unit to finish combines the chunk partials of its
+// heads in a fixed order, so results are bit-reproducible whichever workgroup
+// that happens to be.
 // Logits are kept in the log2 domain: s2 = (q.k) * log2(e)/sqrt(d), p = 2^(s2-m).
 #include "ds_device.h"
 
 namespace ds {
+
+DS_TRACE_BUFFER
 
 struct AttendArgs {
     const _Float16 *q, *K, *V;
@@ -21,6 +25,8 @@ struct AttendArgs {
     const uint32_t *offs;
     int32_t *idx_out;
     float *part;
+    float *out;
+    UnitCtl *ctl_rw;
     int Hq, Hkv, G, L, L_max, key_stride, ch, n_ch, k, k_eff, n_rows;
 };
 
@@ -62,16 +68,16 @@ __device__ __forceinline__ float dot8(half8 a, half8 b)
     return acc;
 }
 
-constexpr float kNegInf = -__builtin_inff();
-
 // MODE 0: rows = tokens of the chunk that pass the selection predicate
 // MODE 1: rows = all tokens of the chunk (dense)
 // MODE 2: rows = pre-gathered [k][2][d] K|V pairs
 template <int GT, int MODE>
-__global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
+__global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 {
-    extern __shared__ int sel[];
-    __shared__ int s_w[4];
+    extern __shared__ int sel[];  // ch words: selected tokens of the chunk (sparse mode only)
+    __shared__ uint32_t s_w[4], s_flag;
+    __shared__ __attribute__((aligned(16))) float red[8][kD];
+    __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT][kD];
     __shared__ __attribute__((aligned(16))) float wpart[4][GT][kPartStride];
 
@@ -81,12 +87,12 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
     const int b = u / a.Hkv, h = u % a.Hkv;
     const int t0 = c * a.ch;
     int n;
+    DS_TR(0);
     if (MODE == 0) {
         const int t1 = min(a.L, t0 + a.ch);
         const uint32_t T = a.ctl[u].T;
         const int tcut = a.ctl[u].tcut;
         n = compact_selected(a.keys + (size_t)u * a.key_stride, t0, t1, T, tcut, sel, s_w);
-        __syncthreads();
         if (a.idx_out) {
             int32_t *io = a.idx_out + (size_t)u * a.k;
             const uint32_t off = a.offs[(size_t)u * a.n_ch + c];
@@ -101,16 +107,18 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
         n = min(a.n_rows, t0 + a.ch) - t0;
     }
 
-    const _Float16 *Ku, *Vu;
-    size_t row_stride;
+    DS_TR(1);
+    // unit base pointers are uniform; a row is addressed by a 32-bit byte offset from them
+    const char *Ku, *Vu;
+    uint32_t row_bytes;
     if (MODE == 2) {
-        Ku = a.K + ((size_t)u * a.k + t0) * 2 * kD + part * 8;
-        Vu = Ku + kD;
-        row_stride = 2 * kD;
+        Ku = reinterpret_cast<const char *>(a.K + ((size_t)u * a.k + t0) * 2 * kD);
+        Vu = Ku + kD * 2;
+        row_bytes = 4 * kD;
     } else {
-        Ku = a.K + (size_t)u * a.L_max * kD + part * 8;
-        Vu = a.V + (size_t)u * a.L_max * kD + part * 8;
-        row_stride = kD;
+        Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
+        Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
+        row_bytes = 2 * kD;
     }
     const float scale_log2 = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
 
@@ -133,22 +141,25 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
         }
 
         for (int r0 = wave * 16; r0 < n; r0 += 64) {
+            // all eight row loads of the pass are issued before the first use; lanes past the
+            // end re-read the last row of the list (in bounds) and mask its score below
             half8 kr[4], vr[4];
             bool ok[4];
+            uint32_t off[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int ri = r0 + i * 4 + slot;
-                ok[i] = ri < n;
-                size_t row = 0;
-                if (ok[i]) row = (MODE == 0) ? (size_t)sel[ri] : (MODE == 1) ? (size_t)(t0 + ri) : (size_t)ri;
-                if (ok[i]) {
-                    kr[i] = *reinterpret_cast<const half8 *>(Ku + row * row_stride);
-                    vr[i] = *reinterpret_cast<const half8 *>(Vu + row * row_stride);
-                } else {
-                    kr[i] = (half8)(_Float16)0;
-                    vr[i] = (half8)(_Float16)0;
-                }
+                const int want = r0 + i * 4 + slot;
+                ok[i] = want < n;
+                const int ri = min(want, n - 1);
+                const uint32_t row = (MODE == 0) ? (uint32_t)sel[ri] : (MODE == 1) ? (uint32_t)(t0 + ri) : (uint32_t)ri;
+                off[i] = row * row_bytes + (uint32_t)part * 16u;
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                kr[i] = *reinterpret_cast<const half8 *>(Ku + off[i]);
+                vr[i] = *reinterpret_cast<const half8 *>(Vu + off[i]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the eight loads ahead of the arithmetic
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
                 const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
@@ -179,6 +190,7 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
             }
         }
 
+        DS_TR(2);
         // merge the four slots of the wave (fixed order), then the four waves
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
@@ -220,33 +232,94 @@ __global__ __launch_bounds__(kWG) void k_attend(AttendArgs a)
                     Ls += f * wpart[w][g][1];
                 }
                 float *po = a.part + (((size_t)u * a.G + g0 + g) * a.n_ch + c) * kPartStride;
-                po[4 + tid] = A;
+                st_dev(po + 4 + tid, A);
                 if (tid == 0) {
-                    po[0] = M;
-                    po[1] = Ls;
+                    st_dev(po + 0, M);
+                    st_dev(po + 1, Ls);
                 }
             }
         }
     }
-}
 
-// Combine the chunk partials of one query head in chunk order:
-// y = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M).
-__global__ __launch_bounds__(kD) void k_merge(const float *__restrict__ part, int n_ch,
-                                              float *__restrict__ out)
-{
-    const int head = blockIdx.x, tid = threadIdx.x;
-    const float *ph = part + (size_t)head * n_ch * kPartStride;
-    float M = kNegInf;
-    for (int c = 0; c < n_ch; ++c) M = fmaxf(M, ph[(size_t)c * kPartStride]);
-    float A = 0.0f, Ls = 0.0f;
-    for (int c = 0; c < n_ch; ++c) {
-        const float mc = ph[(size_t)c * kPartStride];
-        const float f = (mc == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(mc - M);
-        A += f * ph[(size_t)c * kPartStride + 4 + tid];
-        Ls += f * ph[(size_t)c * kPartStride + 1];
+    // ---- last workgroup of the unit: combine the chunk partials of every head of the group.
+    // The workgroup is cut into 8 groups of 32 threads; a group owns 4 output channels per
+    // thread and walks its share of a head's chunks in ascending order with a running
+    // (max, denominator, numerator) state; the `gph` groups of a head are then combined in
+    // group order.  The schedule depends only on (G, n_ch), never on arrival order.
+    DS_TR(3);
+    {
+        const bool last = last_arrival(&a.ctl_rw[u].arrive_c, gridDim.x, &s_flag);
+        DS_TR(4);
+        if (!last) return;
     }
-    out[(size_t)head * kD + tid] = A / Ls;
+    if (tid == 0) a.ctl_rw[u].arrive_c = 0u;
+    const int gph = (a.G >= 8) ? 1 : (a.G >= 4) ? 2 : (a.G >= 2) ? 4 : 8;  // groups per head
+    const int hpr = 8 / gph;                                               // heads per round
+    const int cl = tid >> 5, cg = tid & 31;
+    const int hr = cl / gph, sub = cl % gph;
+    for (int g0 = 0; g0 < a.G; g0 += hpr) {
+        const int g = g0 + hr;
+        float m = kNegInf, l = 0.0f;
+        float4 A = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (g < a.G) {
+            const float *ph = a.part + ((size_t)u * a.G + g) * a.n_ch * kPartStride;
+            for (int c0 = sub; c0 < a.n_ch; c0 += gph * 4) {
+                float2 ml[4];
+                float4 v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int cc = c0 + i * gph;
+                    if (cc < a.n_ch) {
+                        const float *pc = ph + (size_t)cc * kPartStride;
+                        ml[i] = ld_dev(reinterpret_cast<const float2 *>(pc));
+                        const float2 lo = ld_dev(reinterpret_cast<const float2 *>(pc + 4 + cg * 4));
+                        const float2 hi = ld_dev(reinterpret_cast<const float2 *>(pc + 6 + cg * 4));
+                        v[i] = make_float4(lo.x, lo.y, hi.x, hi.y);
+                    } else {
+                        ml[i] = make_float2(kNegInf, 0.f);
+                        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (ml[i].x != kNegInf) {
+                        const float mn = fmaxf(m, ml[i].x);
+                        const float so = (m == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(m - mn);
+                        const float sn = __builtin_amdgcn_exp2f(ml[i].x - mn);
+                        l = l * so + ml[i].y * sn;
+                        A.x = A.x * so + v[i].x * sn;
+                        A.y = A.y * so + v[i].y * sn;
+                        A.z = A.z * so + v[i].z * sn;
+                        A.w = A.w * so + v[i].w * sn;
+                        m = mn;
+                    }
+                }
+            }
+        }
+        *reinterpret_cast<float4 *>(&red[cl][cg * 4]) = A;
+        if (cg == 0) {
+            red_ml[cl][0] = m;
+            red_ml[cl][1] = l;
+        }
+        __syncthreads();
+        for (int hh = tid >> 7; hh < hpr; hh += 2) {
+            const int g2 = g0 + hh, cc = tid & (kD - 1);
+            if (g2 < a.G) {
+                float M = kNegInf;
+                for (int sgi = 0; sgi < gph; ++sgi) M = fmaxf(M, red_ml[hh * gph + sgi][0]);
+                float As = 0.0f, Ls = 0.0f;
+                for (int sgi = 0; sgi < gph; ++sgi) {
+                    const float ms = red_ml[hh * gph + sgi][0];
+                    const float f = (ms == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(ms - M);
+                    As += f * red[hh * gph + sgi][cc];
+                    Ls += f * red_ml[hh * gph + sgi][1];
+                }
+                a.out[((size_t)u * a.G + g2) * kD + cc] = As / Ls;
+            }
+        }
+        __syncthreads();
+    }
+    DS_TR(5);
 }
 
 // ---------------------------------------------------------------- launchers
@@ -271,7 +344,7 @@ static void launch_attend_mode(const AttendArgs &a, dim3 grid, size_t shmem, hip
     }
 }
 
-hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws,
+hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                                 hipStream_t st)
 {
@@ -281,6 +354,8 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     a.V = static_cast<const _Float16 *>(V);
     a.keys = reinterpret_cast<const uint32_t *>(wsp(ws, p.off_keys));
     a.ctl = reinterpret_cast<const UnitCtl *>(wsp(ws, p.off_ctl));
+    a.ctl_rw = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
+    a.out = out;
     a.offs = reinterpret_cast<const uint32_t *>(wsp(ws, p.off_offs));
     a.idx_out = idx_out;
     a.part = reinterpret_cast<float *>(wsp(ws, p.off_part));
@@ -293,7 +368,7 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     return hipGetLastError();
 }
 
-hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws,
+hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st)
 {
     AttendArgs a{};
@@ -301,6 +376,8 @@ hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void
     a.K = static_cast<const _Float16 *>(K);
     a.V = static_cast<const _Float16 *>(V);
     a.part = reinterpret_cast<float *>(wsp(ws, p.off_part));
+    a.ctl_rw = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
+    a.out = out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.ch = p.ch; a.n_ch = p.n_ch;
     prof_begin(KID_DENSE, st);
@@ -309,14 +386,16 @@ hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void
     return hipGetLastError();
 }
 
-hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, const DensePlan &p,
-                              const ds_shape_t &s, int n_rows, hipStream_t st)
+hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,
+                              const DensePlan &p, const ds_shape_t &s, int n_rows, hipStream_t st)
 {
     AttendArgs a{};
     a.q = static_cast<const _Float16 *>(q);
     a.K = static_cast<const _Float16 *>(KV_rows);
     a.V = nullptr;
     a.part = reinterpret_cast<float *>(wsp(ws, p.off_part));
+    a.ctl_rw = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
+    a.out = out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.n_rows = n_rows;
     prof_begin(KID_ATTEND_ROWS, st);
@@ -325,13 +404,12 @@ hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, cons
     return hipGetLastError();
 }
 
-hipError_t launch_merge(const void *part, int n_ch, float *out, int n_heads, hipStream_t st)
-{
-    prof_begin(KID_MERGE, st);
-    hipLaunchKernelGGL(k_merge, dim3(n_heads), dim3(kD), 0, st, static_cast<const float *>(part),
-                       n_ch, out);
-    prof_end(KID_MERGE, st);
-    return hipGetLastError();
-}
-
 }  // namespace ds
+
+#ifdef DS_TRACE
+extern "C" int ds_trace_read_attend(void *dst, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(ds::g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
+

@@ -11,6 +11,24 @@ namespace ds {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 
+constexpr float kNegInf = -__builtin_inff();
+
+// Development aid, compiled out unless the library is built with -DDS_TRACE:
+// thread 0 of every workgroup stamps the device clock at numbered stages into a
+// per-source-file buffer that ds_trace_read_* copies out.
+#ifdef DS_TRACE
+#define DS_TRACE_BUFFER __device__ long long g_trace[1 << 18];
+#define DS_TR(stage)                                                                              \
+    do {                                                                                          \
+        if (threadIdx.x == 0)                                                                     \
+            g_trace[(((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (stage)) & ((1 << 18) - 1)] = \
+                wall_clock64();                                                                   \
+    } while (0)
+#else
+#define DS_TRACE_BUFFER
+#define DS_TR(stage) do { } while (0)
+#endif
+
 // Monotone map from a binary32 score to an unsigned key: a larger score gives a
 // larger key, and -0 maps to the key of +0 so the two tie.
 __device__ __forceinline__ uint32_t score_key(float s)
@@ -28,24 +46,171 @@ __device__ __forceinline__ bool is_selected(uint32_t key, int t, uint32_t T, int
     return key > T || (key == T && t <= tcut);
 }
 
-__device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
+// Data that one workgroup hands to another inside a kernel goes through these
+// device-scope accesses: the stores are written through to the device's
+// coherence point and the loads read it there, so no cache needs flushing.
+// (A device-wide fence per workgroup writes back and invalidates the whole L2
+// of its XCD, which costs far more than the kernels themselves.)
+__device__ __forceinline__ uint32_t ld_dev(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint2 ld_dev(const uint2 *p)
+{
+    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+__device__ __forceinline__ float2 ld_dev(const float2 *p)
+{
+    const uint2 v = ld_dev(reinterpret_cast<const uint2 *>(p));
+    return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
+__device__ __forceinline__ void st_dev(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(float *p, float v)
+{
+    __hip_atomic_store(reinterpret_cast<uint32_t *>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(uint2 *p, uint2 v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p),
+                       (unsigned long long)v.x | ((unsigned long long)v.y << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// "Last workgroup done" hand-over: every workgroup of a group of `total` calls
+// this after its st_dev stores / global atomics; exactly one of them (the last
+// to arrive) gets true in all its threads and may then read what the others
+// wrote with ld_dev.  Each thread first waits until its own stores and atomics
+// have been performed, the barrier collects the workgroup, then one thread
+// bumps the counter.  The counter must be 0 before the first arrival; the
+// workgroup that gets true resets it.
+__device__ __forceinline__ bool last_arrival(uint32_t *counter, uint32_t total, uint32_t *s_flag)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = (t == total - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    return *s_flag != 0u;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront with DPP moves: four
+// shifted adds inside each row of 16 lanes, then the row totals are carried
+// forward (lane 15 of a row into the next row, lane 31 into rows 2 and 3).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_take(int x)
+{
+    // lanes without a source (shifted in from outside the row, or rows masked off) read 0
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int x, int /*lane*/)
+{
+    x += dpp_take<0x111, 0xF>(x);  // row_shr:1
+    x += dpp_take<0x112, 0xF>(x);  // row_shr:2
+    x += dpp_take<0x114, 0xF>(x);  // row_shr:4
+    x += dpp_take<0x118, 0xF>(x);  // row_shr:8
+    x += dpp_take<0x142, 0xA>(x);  // row_bcast:15 into rows 1 and 3
+    x += dpp_take<0x143, 0xC>(x);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// Exclusive prefix sum over the 256 threads of the workgroup (thread order);
+// *total receives the sum.  s_w: 4 words of LDS.  Contains two barriers.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s_w, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t incl = (uint32_t)wave_inclusive_scan((int)x, lane);
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    uint32_t woff = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t c = s_w[w];
+        if (w < wave) woff += c;
+        tot += c;
+    }
+    __syncthreads();
+    *total = tot;
+    return woff + incl - x;
+}
+
+// Fixed-order reductions over the workgroup (same tree every run).
+__device__ __forceinline__ float block_max(float x, float *s_w)
 {
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int y = __shfl_up(x, o);
-        if (lane >= o) x += y;
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = x;
+    __syncthreads();
+    const float r = fmaxf(fmaxf(s_w[0], s_w[1]), fmaxf(s_w[2], s_w[3]));
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_sum(float x, float *s_w)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = x;
+    __syncthreads();
+    const float r = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
+    __syncthreads();
+    return r;
+}
+
+// Histogram select over 256*PER bins whose counts come from get(bin): finds the
+// bin holding the kth element (1-based) counted from the top bin down
+// (FROM_TOP) or from bin 0 up.  res[0] = bin, res[1] = rank of the element
+// inside that bin, counted the same way.  Exactly one thread writes res when
+// 1 <= kth <= total count; all threads may read res after the call.
+template <int PER, bool FROM_TOP, class Get>
+__device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w, uint32_t *res)
+{
+    const int tid = threadIdx.x;
+    constexpr int NB = kWG * PER;
+    uint32_t loc[PER];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int pos = tid * PER + i;
+        loc[i] = get(FROM_TOP ? (NB - 1 - pos) : pos);
+        sum += loc[i];
     }
-    return x;
+    uint32_t total;
+    uint32_t before = block_exclusive_scan(sum, s_w, &total);
+    if (before < kth && before + sum >= kth) {
+        bool done = false;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (!done) {
+                if (before + loc[i] >= kth) {
+                    const int pos = tid * PER + i;
+                    res[0] = (uint32_t)(FROM_TOP ? (NB - 1 - pos) : pos);
+                    res[1] = kth - before;
+                    done = true;
+                } else {
+                    before += loc[i];
+                }
+            }
+        }
+    }
+    __syncthreads();
 }
 
 // Ordered compaction: writes the selected tokens of [t0, t1) to sel[] in
 // ascending token order and returns how many there are (same value in every
 // thread).  keys_u points at the unit's key array; t0 % 4 == 0.  s_w is LDS
-// scratch of 4 ints.  All 256 threads must call it.
+// scratch of 4 words.  All 256 threads must call it.
 __device__ __forceinline__ int compact_selected(const uint32_t *__restrict__ keys_u, int t0, int t1,
-                                                uint32_t T, int tcut, int *sel, int *s_w)
+                                                uint32_t T, int tcut, int *sel, uint32_t *s_w)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     int base = 0;
     for (int p0 = t0; p0 < t1; p0 += kWG * 4) {
         const int t = p0 + tid * 4;
@@ -55,29 +220,20 @@ __device__ __forceinline__ int compact_selected(const uint32_t *__restrict__ key
             kv[0] = v.x; kv[1] = v.y; kv[2] = v.z; kv[3] = v.w;
         }
         bool f[4];
-        int cnt = 0;
+        uint32_t cnt = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             f[e] = (t + e < t1) && is_selected(kv[e], t + e, T, tcut);
-            cnt += f[e] ? 1 : 0;
+            cnt += f[e] ? 1u : 0u;
         }
-        const int incl = wave_inclusive_scan(cnt, lane);
-        if (lane == 63) s_w[wave] = incl;
-        __syncthreads();
-        int woff = 0, total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const int c = s_w[w];
-            if (w < wave) woff += c;
-            total += c;
-        }
-        int pos = base + woff + incl - cnt;
+        uint32_t total;
+        int pos = base + (int)block_exclusive_scan(cnt, s_w, &total);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (f[e]) sel[pos++] = t + e;
-        base += total;
-        __syncthreads();
+        base += (int)total;
     }
+    __syncthreads();
     return base;
 }
 

@@ -19,26 +19,28 @@ constexpr int kKeyShift = 32 - kHistBits;
 constexpr int kPartStride = 132; // floats per attention partial: m, l, 2 pad, acc[128]
 constexpr int kMaxChunks = 8192; // chunk offsets of one unit must fit one workgroup's LDS
 
-// Per-unit selection state in the workspace (64 bytes).
+// Per-unit selection state in the workspace (64 bytes).  The three arrival
+// counters and ncand are zero between calls: the workgroup that consumes one
+// resets it (see ds_workspace_init).
 struct UnitCtl {
-    uint32_t bstar;   // first-level bin holding the k-th largest key
-    uint32_t krem;    // how many keys of that bin are selected (>= 1)
-    uint32_t ncand;   // candidates appended so far (keys in bin bstar)
-    uint32_t T;       // exact k-th largest key
-    int32_t tcut;     // keys equal to T are selected iff token <= tcut
-    uint32_t pad[11];
+    uint32_t bstar;     // first-level bin holding the k-th largest key
+    uint32_t krem;      // how many keys of that bin are selected (>= 1)
+    uint32_t ncand;     // candidates appended so far (keys in bin bstar)
+    uint32_t T;         // exact k-th largest key
+    int32_t tcut;       // keys equal to T are selected iff token <= tcut
+    uint32_t arrive_a;  // workgroups of the scoring kernel that finished this unit
+    uint32_t arrive_b;  // same, candidate kernel
+    uint32_t arrive_c;  // same, attention kernels
+    uint32_t pad[8];
 };
 static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte record");
 
 enum KernelId {
-    KID_ZERO = 0,
+    KID_INIT = 0,
     KID_SCORE,
-    KID_THRESH,
     KID_CAND,
-    KID_REFINE,
     KID_ATTEND,
     KID_COMPACT,
-    KID_MERGE,
     KID_DENSE,
     KID_ATTEND_ROWS,
     KID_LABEL,
@@ -60,7 +62,7 @@ struct Plan {
 struct DensePlan {
     int units, G;
     int ch, n_ch;
-    size_t off_part, total;
+    size_t off_ctl, off_part, total;
 };
 
 bool make_plan(const ds_shape_t &s, Plan *p);
@@ -71,22 +73,20 @@ void prof_begin(int id, hipStream_t st);
 void prof_end(int id, hipStream_t st);
 
 // launchers: enqueue only; return the launch error (hipSuccess if fine)
-hipError_t launch_zero(void *ws, const Plan &p, hipStream_t st);
+hipError_t launch_init(void *ws, size_t bytes, hipStream_t st);
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
                         const Plan &p, const ds_shape_t &s, hipStream_t st);
-hipError_t launch_thresh(void *ws, const Plan &p, hipStream_t st);
-hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st);
-hipError_t launch_refine(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st);
+hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
+                       hipStream_t st);
 hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                           hipStream_t st);
-hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws,
+hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                                 hipStream_t st);
-hipError_t launch_merge(const void *part, int n_ch, float *out, int n_heads, hipStream_t st);
-hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws,
+hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st);
-hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, const DensePlan &p,
-                              const ds_shape_t &s, int n_rows, hipStream_t st);
+hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,
+                              const DensePlan &p, const ds_shape_t &s, int n_rows, hipStream_t st);
 hipError_t launch_label(const void *K, const int32_t *channels, void *label, const ds_shape_t &s,
                         int t0, int n, hipStream_t st);
 hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,

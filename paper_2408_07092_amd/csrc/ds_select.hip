@@ -1,28 +1,31 @@
 // Steps 1-2 of Algorithm 1 on gfx950: label-cache scoring and exact per-unit
-// top-k as a radix select.
+// top-k as a radix select, in two launches.
 //
-//   k_score   streams the label cache, forms the binary32 approximate score of
-//             every token, stores it as an ordered 32-bit key and builds a
-//             4096-bin histogram of the keys' top 12 bits per unit.
-//   k_thresh  finds the histogram bin b* that holds the k-th largest key.
-//   k_cand    collects the keys of bin b* (the only ones whose fate is open)
-//             and counts, per token chunk, the keys above b*.
-//   k_refine  radix-selects the exact k-th key T inside bin b*, resolves equal
-//             keys towards the lowest token index, and turns the per-chunk
-//             counts into offsets of the ascending index list.
-//   k_compact writes that index list (used when the caller wants indices).
+//   k_score  streams the label cache, forms the binary32 approximate score of
+//            every token, stores it as an ordered 32-bit key and builds a
+//            4096-bin histogram of the keys' top 12 bits per unit.  The last
+//            workgroup to finish a unit finds the bin b* that holds the k-th
+//            largest key and clears the histogram for the next call.
+//   k_cand   collects the keys of bin b* (the only ones whose fate is open) and
+//            counts, per token chunk, the keys above b*.  The last workgroup of
+//            a unit radix-selects the exact k-th key T among the candidates,
+//            resolves equal keys towards the lowest token index (tcut), and
+//            turns the per-chunk counts into offsets of the ascending index list.
+//   k_compact writes that index list (for callers that only want indices).
 // All counters are integers, so the result does not depend on the order in
 // which workgroups or atomics complete.
 #include "ds_device.h"
 
 namespace ds {
 
-// ---------------------------------------------------------------- zero
-__global__ __launch_bounds__(kWG) void k_zero(uint32_t *p, size_t n_words)
+DS_TRACE_BUFFER
+
+// ---------------------------------------------------------------- init
+__global__ __launch_bounds__(kWG) void k_init(uint4 *p, size_t n16)
 {
     size_t i = (size_t)blockIdx.x * kWG + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * kWG;
-    for (; i < n_words; i += stride) p[i] = 0u;
+    for (; i < n16; i += stride) p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // ---------------------------------------------------------------- score
@@ -32,16 +35,7 @@ template <int RMODE>
 __device__ __forceinline__ float label_dot(const _Float16 *__restrict__ row, const float *qs, int r)
 {
     float acc = 0.0f;
-    if constexpr (RMODE == 8 || RMODE == 16) {
-        constexpr int NV = RMODE / 8;
-        half8 v[NV];
-#pragma unroll
-        for (int i = 0; i < NV; ++i) v[i] = reinterpret_cast<const half8 *>(row)[i];
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(qs[i * 8 + j], (float)v[i][j], acc);
-    } else if constexpr (RMODE == 0) {
+    if constexpr (RMODE == 0) {
         for (int i = 0; i < r / 8; ++i) {
             const half8 v = reinterpret_cast<const half8 *>(row)[i];
 #pragma unroll
@@ -57,135 +51,154 @@ template <int RMODE>
 __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                                                const _Float16 *__restrict__ label,
                                                const int32_t *__restrict__ channels,
-                                               uint32_t *__restrict__ keys,
-                                               uint32_t *__restrict__ hist, int Hq, int Hkv, int G,
-                                               int L, int L_max, int r, int key_stride, int sc_chunk)
+                                               uint32_t *__restrict__ keys, uint32_t *hist,
+                                               UnitCtl *ctl, int Hq, int Hkv, int G, int L, int L_max,
+                                               int r, int key_stride, int sc_chunk, int k_eff)
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ float qs_sh[kD];
+    __shared__ uint32_t s_w[4], s_res[2], s_flag;
     const int tid = threadIdx.x;
     const int u = blockIdx.y, b = u / Hkv, h = u % Hkv;
-
-    for (int i = tid; i < kHistBins; i += kWG) lh[i] = 0u;
-    if (tid < r) {
-        // label query of the group: sum over its heads (g ascending) of q_g[C[j]]
-        const int c = channels[h * r + tid];
-        float a = 0.0f;
-        for (int g = 0; g < G; ++g) a = a + (float)q[((size_t)b * Hq + (size_t)h * G + g) * kD + c];
-        qs_sh[tid] = a;
-    }
-    __syncthreads();
-
-    float qs[(RMODE > 0) ? RMODE : 1];
-    if (RMODE > 0) {
-#pragma unroll
-        for (int j = 0; j < ((RMODE > 0) ? RMODE : 1); ++j) qs[j] = qs_sh[j];
-    }
-    const float *qp = (RMODE > 0) ? qs : qs_sh;
-
     const int t_begin = blockIdx.x * sc_chunk;
     const int t_end = min(L, t_begin + sc_chunk);
     const _Float16 *lab = label + (size_t)u * L_max * r;
     uint32_t *ku = keys + (size_t)u * key_stride;
 
-    constexpr int UNR = 4;
-    for (int t0 = t_begin + tid; t0 < t_end; t0 += kWG * UNR) {
-        float s[UNR];
+    // Fast modes: eight tokens per thread per pass, every load of a pass issued before the
+    // first use; lanes past the end re-read the chunk's last token (in bounds) and drop the
+    // result.  The first pass is put in flight before the label query is formed.
+    constexpr int NV = (RMODE > 0) ? RMODE / 8 : 1;
+    constexpr int UNR = 8;
+    half8 v[UNR][NV];
+    auto issue = [&](int t0) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
-            const int t = t0 + i * kWG;
-            s[i] = (t < t_end) ? label_dot<RMODE>(lab + (size_t)t * r, qp, r) : 0.0f;
-        }
+            const int t = min(t0 + i * kWG, t_end - 1);
+            const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)t * (NV * 8));
 #pragma unroll
-        for (int i = 0; i < UNR; ++i) {
-            const int t = t0 + i * kWG;
-            if (t < t_end) {
-                const uint32_t key = score_key(s[i]);
-                ku[t] = key;
-                atomicAdd(&lh[key >> kKeyShift], 1u);
-            }
+            for (int j = 0; j < NV; ++j) v[i][j] = row[j];
         }
+    };
+    DS_TR(0);
+    // Label query of the group: sum over its heads (g ascending) of q_g[C[j]].  Threads
+    // [128, 128 + r) fetch it; the two dependent loads (channel id, then q) are started
+    // before the label loads so that they complete first, the rest of the sum follows.
+    const int j_q = tid - 128;
+    const bool has_q = j_q >= 0 && j_q < r;
+    int c_q = 0;
+    _Float16 q0 = (_Float16)0;
+    if (has_q) {
+        c_q = channels[h * r + j_q];
+        q0 = q[((size_t)b * Hq + (size_t)h * G) * kD + c_q];
+    }
+    if constexpr (RMODE > 0) {
+        issue(t_begin + tid);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (int i = tid; i < kHistBins; i += kWG) lh[i] = 0u;
+    if (has_q) {
+        float a = 0.0f + (float)q0;
+        for (int g = 1; g < G; ++g) a = a + (float)q[((size_t)b * Hq + (size_t)h * G + g) * kD + c_q];
+        qs_sh[j_q] = a;
     }
     __syncthreads();
-    uint32_t *hu = hist + (size_t)u * kHistBins;
-    for (int i = tid; i < kHistBins; i += kWG) {
-        const uint32_t c = lh[i];
-        if (c) atomicAdd(&hu[i], c);
-    }
-}
 
-// ---------------------------------------------------------------- histogram select
-// LDS histogram lh[256*PER]; finds the bin holding the kth element (1-based)
-// counted from the top bin down (FROM_TOP) or from bin 0 up.  res[0] = bin,
-// res[1] = rank of the element inside that bin, counted the same way.
-// Exactly one thread writes res when 1 <= kth <= total count.
-template <int PER, bool FROM_TOP>
-__device__ __forceinline__ void hist_select(const uint32_t *lh, uint32_t kth, uint32_t *s_part,
-                                            uint32_t *res)
-{
-    const int tid = threadIdx.x;
-    constexpr int NB = kWG * PER;
-    uint32_t loc[PER];
-    uint32_t sum = 0;
+    DS_TR(1);
+    if constexpr (RMODE > 0) {
+        float qs[RMODE];
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int pos = tid * PER + i;
-        loc[i] = lh[FROM_TOP ? (NB - 1 - pos) : pos];
-        sum += loc[i];
-    }
-    s_part[tid] = sum;
-    __syncthreads();
-    uint32_t before = 0;
-    for (int j = 0; j < tid; ++j) before += s_part[j];
-    if (before < kth && before + sum >= kth) {
-        bool done = false;
+        for (int j = 0; j < RMODE; ++j) qs[j] = qs_sh[j];
+        for (int t0 = t_begin + tid; t0 < t_end;) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            if (!done) {
-                if (before + loc[i] >= kth) {
-                    const int pos = tid * PER + i;
-                    res[0] = (uint32_t)(FROM_TOP ? (NB - 1 - pos) : pos);
-                    res[1] = kth - before;
-                    done = true;
-                } else {
-                    before += loc[i];
+            for (int i = 0; i < UNR; ++i) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int j = 0; j < NV; ++j)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
+                const int t = t0 + i * kWG;
+                if (t < t_end) {
+                    const uint32_t key = score_key(acc);
+                    ku[t] = key;
+                    atomicAdd(&lh[key >> kKeyShift], 1u);
                 }
             }
+            t0 += kWG * UNR;
+            if (t0 < t_end) issue(t0);
+        }
+    } else {
+        for (int t = t_begin + tid; t < t_end; t += kWG) {
+            const uint32_t key = score_key(label_dot<RMODE>(lab + (size_t)t * r, qs_sh, r));
+            ku[t] = key;
+            atomicAdd(&lh[key >> kKeyShift], 1u);
         }
     }
+    DS_TR(2);
     __syncthreads();
-}
-
-__global__ __launch_bounds__(kWG) void k_thresh(const uint32_t *__restrict__ hist, UnitCtl *ctl,
-                                                int k_eff)
-{
-    __shared__ uint32_t lh[kHistBins];
-    __shared__ uint32_t s_part[kWG];
-    __shared__ uint32_t res[2];
-    const int tid = threadIdx.x, u = blockIdx.x;
-    const uint32_t *hu = hist + (size_t)u * kHistBins;
-    for (int i = tid; i < kHistBins; i += kWG) lh[i] = hu[i];
-    __syncthreads();
-    hist_select<kHistBins / kWG, true>(lh, (uint32_t)k_eff, s_part, res);
-    if (tid == 0) {
-        ctl[u].bstar = res[0];
-        ctl[u].krem = res[1];
+    uint32_t *hu = hist + (size_t)u * kHistBins;
+    {
+        uint32_t c[kHistBins / kWG];
+#pragma unroll
+        for (int i = 0; i < kHistBins / kWG; ++i) c[i] = lh[tid + i * kWG];
+#pragma unroll
+        for (int i = 0; i < kHistBins / kWG; ++i)
+            if (c[i]) atomicAdd(&hu[tid + i * kWG], c[i]);
     }
+
+    // ---- last workgroup of the unit: threshold bin, then leave the histogram clean
+    DS_TR(3);
+    {
+        const bool last = last_arrival(&ctl[u].arrive_a, gridDim.x, &s_flag);
+        DS_TR(4);
+        if (!last) return;
+    }
+    hist_select<kHistBins / kWG, true>([&](int bin) { return ld_dev(hu + bin); }, (uint32_t)k_eff, s_w,
+                                       s_res);
+    DS_TR(5);
+    if (tid == 0) {
+        ctl[u].bstar = s_res[0];
+        ctl[u].krem = s_res[1];
+        ctl[u].arrive_a = 0u;
+    }
+    for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
+    DS_TR(6);
 }
 
-// ---------------------------------------------------------------- candidates
-__global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys, UnitCtl *ctl,
-                                              uint2 *__restrict__ cand, uint32_t *__restrict__ ndef,
-                                              int L, int key_stride, int ch, int n_ch)
+// ---------------------------------------------------------------- candidates + exact threshold
+// One radix pass of the refinement: histogram `digit(e)` over the candidates
+// that satisfy `match(e)`, then pick the bin holding the `want`-th of them.
+template <int PER, bool FROM_TOP, class At, class Match, class Digit>
+__device__ __forceinline__ void radix_pass(uint32_t n, At at, Match match, Digit digit, uint32_t want,
+                                           uint32_t *lh, uint32_t *s_w, uint32_t *res)
 {
-    extern __shared__ uint2 lc[];  // ch entries
-    __shared__ uint32_t s_cnt, s_def, s_base;
+    for (int i = threadIdx.x; i < kWG * PER; i += kWG) lh[i] = 0u;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n; i += kWG) {
+        const uint2 e = at(i);
+        if (match(e)) atomicAdd(&lh[digit(e)], 1u);
+    }
+    __syncthreads();
+    hist_select<PER, FROM_TOP>([&](int bin) { return lh[bin]; }, want, s_w, res);
+}
+
+__global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys, UnitCtl *ctl,
+                                              uint2 *cand, uint32_t *ndef, uint32_t *offs, int L,
+                                              int key_stride, int ch, int n_ch, int cap_lds,
+                                              int want_offsets)
+{
+    extern __shared__ uint2 lc[];  // cap_lds candidate slots, then n_ch counters
+    __shared__ uint32_t lh[2048];
+    __shared__ uint32_t s_cnt, s_def, s_base, s_flag;
+    __shared__ uint32_t s_w[4], s_res[2];
     const int tid = threadIdx.x, u = blockIdx.y, c = blockIdx.x;
     if (tid == 0) { s_cnt = 0u; s_def = 0u; }
     __syncthreads();
+    DS_TR(8);
     const uint32_t bstar = ctl[u].bstar;
     const int t0 = c * ch, t1 = min(L, t0 + ch);
     const uint32_t *ku = keys + (size_t)u * key_stride;
+    uint2 *cu = cand + (size_t)u * L;
     uint32_t mydef = 0;
     for (int t = t0 + tid * 4; t < t1; t += kWG * 4) {
         const uint4 v = *reinterpret_cast<const uint4 *>(ku + t);
@@ -197,120 +210,97 @@ __global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys,
                 if (bin > bstar) {
                     ++mydef;
                 } else if (bin == bstar) {
-                    const uint32_t slot = atomicAdd(&s_cnt, 1u);
+                    const uint32_t slot = atomicAdd(&s_cnt, 1u);  // slot < tokens of the chunk <= ch
                     lc[slot] = make_uint2(kv[e], (uint32_t)(t + e));
                 }
             }
         }
     }
-    if (mydef) atomicAdd(&s_def, mydef);
+    DS_TR(9);
+    if (want_offsets && mydef) atomicAdd(&s_def, mydef);
     __syncthreads();
     if (tid == 0) {
-        ndef[(size_t)u * n_ch + c] = s_def;
+        if (want_offsets) st_dev(ndef + (size_t)u * n_ch + c, s_def);
         s_base = s_cnt ? atomicAdd(&ctl[u].ncand, s_cnt) : 0u;
     }
     __syncthreads();
-    const uint32_t n = s_cnt, base = s_base;
-    uint2 *cu = cand + (size_t)u * L;
-    for (uint32_t i = tid; i < n; i += kWG) cu[base + i] = lc[i];
-}
+    {
+        const uint32_t n = s_cnt, base = s_base;
+        for (uint32_t i = tid; i < n; i += kWG) st_dev(cu + base + i, lc[i]);
+    }
 
-// ---------------------------------------------------------------- refine
-__global__ __launch_bounds__(kWG) void k_refine(const uint2 *__restrict__ cand, UnitCtl *ctl,
-                                                const uint32_t *__restrict__ ndef,
-                                                uint32_t *__restrict__ offs, int L, int ch, int n_ch)
-{
-    __shared__ uint32_t lh[2048];
-    __shared__ uint32_t s_part[kWG];
-    __shared__ uint32_t res[2];
-    extern __shared__ uint32_t cnt[];  // n_ch entries
-    const int tid = threadIdx.x, u = blockIdx.x;
-    const uint2 *cu = cand + (size_t)u * L;
-    const uint32_t n = ctl[u].ncand;
-    const uint32_t bstar = ctl[u].bstar;
+    // ---- last workgroup of the unit: exact k-th key among the candidates
+    DS_TR(10);
+    {
+        const bool last = last_arrival(&ctl[u].arrive_b, gridDim.x, &s_flag);
+        DS_TR(11);
+        if (!last) return;
+    }
+    const uint32_t n = ld_dev(&ctl[u].ncand);
+    const bool in_lds = n <= (uint32_t)cap_lds;
+    if (in_lds)
+        for (uint32_t i = tid; i < n; i += kWG) lc[i] = ld_dev(cu + i);
+    __syncthreads();
+    auto at = [&](uint32_t i) { return in_lds ? lc[i] : ld_dev(cu + i); };
+    DS_TR(12);
     uint32_t krem = ctl[u].krem;
 
-    // key bits [19:10] of the candidates (all share the top 12 bits)
-    for (int i = tid; i < 1024; i += kWG) lh[i] = 0u;
+    // key bits [19:10] (all candidates share the top 12 bits), then bits [9:0]
+    radix_pass<4, true>(n, at, [](uint2) { return true; },
+                        [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
+    const uint32_t pre22 = (bstar << 10) | s_res[0];
+    krem = s_res[1];
     __syncthreads();
-    for (uint32_t i = tid; i < n; i += kWG) atomicAdd(&lh[(cu[i].x >> 10) & 1023u], 1u);
-    __syncthreads();
-    hist_select<4, true>(lh, krem, s_part, res);
-    const uint32_t mid = res[0];
-    krem = res[1];
-    __syncthreads();
-    // key bits [9:0] among candidates matching so far
-    for (int i = tid; i < 1024; i += kWG) lh[i] = 0u;
-    __syncthreads();
-    const uint32_t pre22 = (bstar << 10) | mid;
-    for (uint32_t i = tid; i < n; i += kWG) {
-        const uint32_t key = cu[i].x;
-        if ((key >> 10) == pre22) atomicAdd(&lh[key & 1023u], 1u);
-    }
-    __syncthreads();
-    hist_select<4, true>(lh, krem, s_part, res);
-    const uint32_t T = (pre22 << 10) | res[0];
-    const uint32_t m_ties = res[1];          // how many keys equal to T are selected
-    const uint32_t n_ties = lh[res[0]];      // how many keys equal T
+    radix_pass<4, true>(n, at, [&](uint2 e) { return (e.x >> 10) == pre22; },
+                        [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
+    const uint32_t T = (pre22 << 10) | s_res[0];
+    const uint32_t m_ties = s_res[1];       // how many keys equal to T are selected
+    const uint32_t n_ties = lh[s_res[0]];   // how many keys equal T
     __syncthreads();
 
-    // Equal keys: keep the m_ties lowest token indices -> tcut = m_ties-th smallest
+    // Equal keys: keep the m_ties lowest token indices -> tcut = the m_ties-th smallest
     // index among them (radix select on the index, 11 + 10 + 10 bits, ascending).
     int tcut = 0x7fffffff;
     if (m_ties < n_ties) {
-        uint32_t want = m_ties, prefix = 0u;
-        // bits [30:20]
-        for (int i = tid; i < 2048; i += kWG) lh[i] = 0u;
+        radix_pass<8, false>(n, at, [&](uint2 e) { return e.x == T; },
+                             [](uint2 e) { return e.y >> 20; }, m_ties, lh, s_w, s_res);
+        uint32_t prefix = s_res[0], want = s_res[1];
         __syncthreads();
-        for (uint32_t i = tid; i < n; i += kWG)
-            if (cu[i].x == T) atomicAdd(&lh[cu[i].y >> 20], 1u);
+        radix_pass<4, false>(n, at, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+                             [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
+        prefix = (prefix << 10) | s_res[0];
+        want = s_res[1];
         __syncthreads();
-        hist_select<8, false>(lh, want, s_part, res);
-        prefix = res[0];
-        want = res[1];
-        __syncthreads();
-        // bits [19:10]
-        for (int i = tid; i < 1024; i += kWG) lh[i] = 0u;
-        __syncthreads();
-        for (uint32_t i = tid; i < n; i += kWG)
-            if (cu[i].x == T && (cu[i].y >> 20) == prefix) atomicAdd(&lh[(cu[i].y >> 10) & 1023u], 1u);
-        __syncthreads();
-        hist_select<4, false>(lh, want, s_part, res);
-        prefix = (prefix << 10) | res[0];
-        want = res[1];
-        __syncthreads();
-        // bits [9:0]
-        for (int i = tid; i < 1024; i += kWG) lh[i] = 0u;
-        __syncthreads();
-        for (uint32_t i = tid; i < n; i += kWG)
-            if (cu[i].x == T && (cu[i].y >> 10) == prefix) atomicAdd(&lh[cu[i].y & 1023u], 1u);
-        __syncthreads();
-        hist_select<4, false>(lh, want, s_part, res);
-        tcut = (int)((prefix << 10) | res[0]);
+        radix_pass<4, false>(n, at, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+                             [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
+        tcut = (int)((prefix << 10) | s_res[0]);
         __syncthreads();
     }
+    DS_TR(13);
     if (tid == 0) {
         ctl[u].T = T;
         ctl[u].tcut = tcut;
+        ctl[u].ncand = 0u;
+        ctl[u].arrive_b = 0u;
     }
+    if (!want_offsets) return;
 
-    // selected tokens per chunk = keys above bin b* (ndef) + selected candidates
-    for (int i = tid; i < n_ch; i += kWG) cnt[i] = ndef[(size_t)u * n_ch + i];
+    // selected tokens per chunk = keys above bin b* (ndef) + selected candidates;
+    // exclusive prefix over chunks -> offsets into the ascending index list
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(lc + cap_lds);
+    for (int i = tid; i < n_ch; i += kWG) cnt[i] = ld_dev(ndef + (size_t)u * n_ch + i);
     __syncthreads();
     for (uint32_t i = tid; i < n; i += kWG) {
-        const uint2 e = cu[i];
+        const uint2 e = at(i);
         if (is_selected(e.x, (int)e.y, T, tcut)) atomicAdd(&cnt[e.y / (uint32_t)ch], 1u);
     }
     __syncthreads();
-    // exclusive prefix over chunks -> offsets into the ascending index list
     const int per = (n_ch + kWG - 1) / kWG;
-    const int c0 = tid * per, c1 = min(n_ch, c0 + per);
+    const int c0 = min(n_ch, tid * per), c1 = min(n_ch, c0 + per);
     uint32_t sum = 0;
     for (int i = c0; i < c1; ++i) sum += cnt[i];
-    s_part[tid] = sum;
-    __syncthreads();
-    uint32_t run = 0;
-    for (int j = 0; j < tid; ++j) run += s_part[j];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, s_w, &total);
     for (int i = c0; i < c1; ++i) {
         offs[(size_t)u * n_ch + i] = run;
         run += cnt[i];
@@ -326,13 +316,12 @@ __global__ __launch_bounds__(kWG) void k_compact(const uint32_t *__restrict__ ke
                                                  int ch, int n_ch, int k, int k_eff)
 {
     extern __shared__ int sel[];  // ch entries
-    __shared__ int s_w[4];
+    __shared__ uint32_t s_w[4];
     const int tid = threadIdx.x, u = blockIdx.y, c = blockIdx.x;
     const int t0 = c * ch, t1 = min(L, t0 + ch);
     const uint32_t T = ctl[u].T;
     const int tcut = ctl[u].tcut;
     const int n = compact_selected(keys + (size_t)u * key_stride, t0, t1, T, tcut, sel, s_w);
-    __syncthreads();
     int32_t *io = idx_out + (size_t)u * k;
     const uint32_t off = offs[(size_t)u * n_ch + c];
     for (int i = tid; i < n; i += kWG)
@@ -344,15 +333,15 @@ __global__ __launch_bounds__(kWG) void k_compact(const uint32_t *__restrict__ ke
 // ---------------------------------------------------------------- launchers
 static inline char *wsp(void *ws, size_t off) { return static_cast<char *>(ws) + off; }
 
-hipError_t launch_zero(void *ws, const Plan &p, hipStream_t st)
+hipError_t launch_init(void *ws, size_t bytes, hipStream_t st)
 {
-    // ctl and hist are adjacent in the workspace
-    const size_t n_words = (p.off_keys - p.off_ctl) / 4;
-    const int blocks = (int)((n_words + kWG * 4 - 1) / (kWG * 4));
-    prof_begin(KID_ZERO, st);
-    hipLaunchKernelGGL(k_zero, dim3(blocks < 1 ? 1 : blocks), dim3(kWG), 0, st,
-                       reinterpret_cast<uint32_t *>(wsp(ws, p.off_ctl)), n_words);
-    prof_end(KID_ZERO, st);
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + kWG * 4 - 1) / (kWG * 4);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 65536) blocks = 65536;
+    prof_begin(KID_INIT, st);
+    hipLaunchKernelGGL(k_init, dim3((unsigned)blocks), dim3(kWG), 0, st, static_cast<uint4 *>(ws), n16);
+    prof_end(KID_INIT, st);
     return hipGetLastError();
 }
 
@@ -362,12 +351,13 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     const dim3 grid(p.n_sc, p.units), block(kWG);
     auto *keys = reinterpret_cast<uint32_t *>(wsp(ws, p.off_keys));
     auto *hist = reinterpret_cast<uint32_t *>(wsp(ws, p.off_hist));
+    auto *ctl = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
     const auto *qh = static_cast<const _Float16 *>(q);
     const auto *lh = static_cast<const _Float16 *>(label);
     prof_begin(KID_SCORE, st);
-#define DS_SCORE(MODE)                                                                         \
-    hipLaunchKernelGGL(k_score<MODE>, grid, block, 0, st, qh, lh, channels, keys, hist, s.Hq,   \
-                       s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk)
+#define DS_SCORE(MODE)                                                                            \
+    hipLaunchKernelGGL(k_score<MODE>, grid, block, 0, st, qh, lh, channels, keys, hist, ctl, s.Hq, \
+                       s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk, p.k_eff)
     if (s.r == 8) DS_SCORE(8);
     else if (s.r == 16) DS_SCORE(16);
     else if (s.r % 8 == 0) DS_SCORE(0);
@@ -377,38 +367,20 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     return hipGetLastError();
 }
 
-hipError_t launch_thresh(void *ws, const Plan &p, hipStream_t st)
+hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
+                       hipStream_t st)
 {
-    prof_begin(KID_THRESH, st);
-    hipLaunchKernelGGL(k_thresh, dim3(p.units), dim3(kWG), 0, st,
-                       reinterpret_cast<const uint32_t *>(wsp(ws, p.off_hist)),
-                       reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl)), p.k_eff);
-    prof_end(KID_THRESH, st);
-    return hipGetLastError();
-}
-
-hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st)
-{
+    const int cap_lds = p.ch > 2048 ? p.ch : 2048;
+    const size_t shmem = (size_t)cap_lds * sizeof(uint2) + (size_t)p.n_ch * sizeof(uint32_t);
     prof_begin(KID_CAND, st);
-    hipLaunchKernelGGL(k_cand, dim3(p.n_ch, p.units), dim3(kWG), (size_t)p.ch * sizeof(uint2), st,
+    hipLaunchKernelGGL(k_cand, dim3(p.n_ch, p.units), dim3(kWG), shmem, st,
                        reinterpret_cast<const uint32_t *>(wsp(ws, p.off_keys)),
                        reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl)),
                        reinterpret_cast<uint2 *>(wsp(ws, p.off_cand)),
-                       reinterpret_cast<uint32_t *>(wsp(ws, p.off_ndef)), s.L, p.key_stride, p.ch,
-                       p.n_ch);
+                       reinterpret_cast<uint32_t *>(wsp(ws, p.off_ndef)),
+                       reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs)), s.L, p.key_stride, p.ch,
+                       p.n_ch, cap_lds, want_offsets ? 1 : 0);
     prof_end(KID_CAND, st);
-    return hipGetLastError();
-}
-
-hipError_t launch_refine(void *ws, const Plan &p, const ds_shape_t &s, hipStream_t st)
-{
-    prof_begin(KID_REFINE, st);
-    hipLaunchKernelGGL(k_refine, dim3(p.units), dim3(kWG), (size_t)p.n_ch * sizeof(uint32_t), st,
-                       reinterpret_cast<const uint2 *>(wsp(ws, p.off_cand)),
-                       reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl)),
-                       reinterpret_cast<const uint32_t *>(wsp(ws, p.off_ndef)),
-                       reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs)), s.L, p.ch, p.n_ch);
-    prof_end(KID_REFINE, st);
     return hipGetLastError();
 }
 
@@ -426,3 +398,11 @@ hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_sh
 }
 
 }  // namespace ds
+
+#ifdef DS_TRACE
+extern "C" int ds_trace_read_select(void *dst, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(ds::g_trace), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
+

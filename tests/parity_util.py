@@ -44,9 +44,7 @@ class Case:
         self.ch = to_dev(self.ch_h)
         self.shape = ds.shape(self.B, self.Hq, self.Hkv, self.d, L, self.L_max, self.r, k)
         self.label = torch.zeros((self.B, self.Hkv, self.L_max, self.r), dtype=torch.float16, device="cuda")
-        ws_bytes = ds.ds_workspace_bytes(self.shape)
-        assert ws_bytes > 0
-        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.ws = ds.ds_workspace_alloc(self.shape)
 
     @classmethod
     def from_torch(cls, t, channels, L, k):
@@ -61,7 +59,7 @@ class Case:
         self.ch = to_dev(self.ch_h)
         self.shape = ds.shape(self.B, self.Hq, self.Hkv, self.d, L, self.L_max, self.r, k)
         self.label = torch.zeros((self.B, self.Hkv, self.L_max, self.r), dtype=torch.float16, device="cuda")
-        self.ws = torch.empty(ds.ds_workspace_bytes(self.shape), dtype=torch.uint8, device="cuda")
+        self.ws = ds.ds_workspace_alloc(self.shape)
         return self
 
     # ---- HIP path

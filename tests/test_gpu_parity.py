@@ -251,7 +251,7 @@ def test_full_config_c5_offload_rows_from_pinned_host():
     torch.cuda.synchronize()
     lab_ref = O.build_label(K_h, ch, w.L)
     assert np.array_equal(label.cpu().numpy().view(np.uint16), lab_ref.view(np.uint16))
-    ws = torch.empty(ds.ds_workspace_bytes(shp), dtype=torch.uint8, device="cuda")
+    ws = ds.ds_workspace_alloc(shp)
     idx = torch.empty((w.B, w.Hkv, w.k), dtype=torch.int32, device="cuda")
     rows = torch.empty((w.B, w.Hkv, w.k, 2, w.d), dtype=torch.float16, device="cuda")
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")

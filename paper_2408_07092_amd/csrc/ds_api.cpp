@@ -13,8 +13,8 @@
 namespace ds {
 
 // ---------------------------------------------------------------- knobs
-static int g_tune[3] = {0, 0, 0};
-int tune_get(int knob) { return (knob >= 0 && knob < 3) ? g_tune[knob] : 0; }
+static int g_tune[4] = {0, 0, 0, 0};
+int tune_get(int knob) { return (knob >= 0 && knob < 4) ? g_tune[knob] : 0; }
 
 // ---------------------------------------------------------------- plans
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -57,12 +57,15 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     size_t off = 0;
     p->off_ctl = off;   off = align_up(off + (size_t)p->units * sizeof(UnitCtl), 256);
     p->off_hist = off;  off = align_up(off + (size_t)p->units * kHistBins * 4, 256);
+    p->off_coarse = off; off = align_up(off + (size_t)p->units * 256 * 4, 256);
     p->off_keys = off;  off = align_up(off + (size_t)p->units * p->key_stride * 4, 256);
     p->off_cand = off;  off = align_up(off + (size_t)p->units * s.L * 8, 256);
     p->off_ndef = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
     p->off_offs = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
     p->off_part = off;  off = align_up(off + (size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
-    p->total = off;
+    // the single-launch path shares the control prefix and lays its own data after it
+    p->off_fused = p->off_keys;
+    p->total = std::max(off, align_up(p->off_fused + fused_workspace_bytes(s, *p), 256));
     return true;
 }
 
@@ -83,6 +86,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
     size_t off = 0;
     p->off_ctl = off;   off = align_up(off + (size_t)p->units * sizeof(UnitCtl), 256);
     off = align_up(off + (size_t)p->units * kHistBins * 4, 256);
+    off = align_up(off + (size_t)p->units * 256 * 4, 256);
     p->off_part = off;  off = align_up(off + (size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
     p->total = off;
     return true;
@@ -91,7 +95,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 // ---------------------------------------------------------------- per-kernel event timing
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
-    "k_attend_rows", "k_label", "k_gather_host", "k_probe"};
+    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -290,6 +294,11 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
     if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
+    FusedPlan f;
+    if (make_fused_plan(*shape, p, &f)) {
+        DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
+        return DS_OK;
+    }
     rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st);
     if (rc != DS_OK) return rc;
     DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st));
@@ -411,12 +420,13 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches)
 
 ds_status_t ds_tune_set(int knob, int value)
 {
-    if (knob < 0 || knob > 2) return DS_ERR_SHAPE;
+    if (knob < 0 || knob > 3) return DS_ERR_SHAPE;
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 1 && (value % 256 != 0 || value > 4096)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
+        if (knob == 3 && value > 2) return DS_ERR_SHAPE;
     }
     g_tune[knob] = value;
     return DS_OK;

@@ -1,0 +1,265 @@
+// Attention building blocks shared by the per-chunk attention kernel and the
+// fused decode kernel (Algorithm 1 steps 3-5 / Sec. 2.1).
+//
+// Row processing: a wavefront loads four rows per instruction -- 16 lanes x 16
+// bytes cover one 256-byte row -- so each 16-lane group ("slot") owns a row at
+// a time and keeps its own online-softmax state (running max m, denominator l,
+// 8 output channels per lane).  Logits live in the log2 domain:
+// s2 = (q.k) * log2(e)/sqrt(d), p = 2^(s2 - m).
+// Every reduction runs in an order fixed by the launch shape, so results are
+// bit-reproducible.
+#pragma once
+
+#include "ds_device.h"
+
+namespace ds {
+
+constexpr float kScaleLog2 = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+__device__ __forceinline__ float dpp_add(float v, float moved) { return v + moved; }
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// Sum over the 16 lanes of a row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    v += dpp_move<0x140>(v);  // row_mirror
+    return v;
+}
+
+__device__ __forceinline__ float dot8(half8 a, half8 b)
+{
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        half2v x = {a[2 * i], a[2 * i + 1]};
+        half2v y = {b[2 * i], b[2 * i + 1]};
+        acc = __builtin_amdgcn_fdot2(x, y, acc, false);
+    }
+    return acc;
+}
+
+template <int GT>
+struct RowState {
+    float m[GT], l[GT], acc[GT][8];
+    __device__ __forceinline__ void init()
+    {
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            m[g] = kNegInf;
+            l[g] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[g][j] = 0.0f;
+        }
+    }
+};
+
+// The calling wavefront's share of the workgroup's n rows: rows wave*16 + 64*i ..
+// row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
+// Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
+template <int GT, class RowOf>
+__device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
+                                            RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int slot = lane >> 4, part = lane & 15;
+    for (int r0 = wave * 16; r0 < n; r0 += 64) {
+        // all eight row loads of the pass are issued before the first use; lanes past the
+        // end re-read the last row of the list (in bounds) and mask its score below
+        half8 kr[4], vr[4];
+        bool ok[4];
+        uint32_t off[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int want = r0 + i * 4 + slot;
+            ok[i] = want < n;
+            off[i] = (uint32_t)row_of(min(want, n - 1)) * row_bytes + (uint32_t)part * 16u;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            kr[i] = *reinterpret_cast<const half8 *>(Ku + off[i]);
+            vr[i] = *reinterpret_cast<const half8 *>(Vu + off[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the eight loads ahead of the arithmetic
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
+            float s[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                s[i] = row16_sum(dot8(qv, kr[i])) * kScaleLog2;
+                if (!ok[i]) s[i] = kNegInf;
+            }
+            // a slot may have no valid row yet (m stays -inf); slot 0 always has one here
+            const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+            const float mn = fmaxf(st.m[g], mx);
+            if (mn != kNegInf) {
+                const float sc = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mn);
+                st.m[g] = mn;
+                st.l[g] *= sc;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) st.acc[g][j] *= sc;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(s[i] - mn);  // 2^-inf = 0 for masked rows
+                    st.l[g] += p;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        st.acc[g][j] = __builtin_fmaf(p, (float)vr[i][j], st.acc[g][j]);
+                }
+            }
+        }
+    }
+}
+
+// Merges the 16 slot states of the workgroup (4 slots per wave in slot order,
+// then the 4 waves in wave order) and writes one partial {m, l, -, -, acc[128]}
+// per head g to po + g * head_stride with device-scope stores.
+// wpart: LDS [4][GT][kPartStride].  Contains one barrier; callers must put a
+// barrier between two uses of wpart.
+template <int GT>
+__device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
+                                                 float (*wpart)[GT][kPartStride], float *po,
+                                                 size_t head_stride)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int slot = lane >> 4, part = lane & 15;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+        float mm = fmaxf(st.m[g], __shfl_xor(st.m[g], 16));
+        mm = fmaxf(mm, __shfl_xor(mm, 32));
+        const float w = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mm);
+        float lv = st.l[g] * w;
+        lv += __shfl_xor(lv, 16);
+        lv += __shfl_xor(lv, 32);
+        float av[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            av[j] = st.acc[g][j] * w;
+            av[j] += __shfl_xor(av[j], 16);
+            av[j] += __shfl_xor(av[j], 32);
+        }
+        if (slot == 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wpart[wave][g][4 + part * 8 + j] = av[j];
+            if (part == 0) {
+                wpart[wave][g][0] = mm;
+                wpart[wave][g][1] = lv;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kD) {
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            float M = kNegInf;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][g][0]);
+            float A = 0.0f, Ls = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float mw = wpart[w][g][0];
+                const float f = (mw == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(mw - M);
+                A += f * wpart[w][g][4 + tid];
+                Ls += f * wpart[w][g][1];
+            }
+            float *pg = po + (size_t)g * head_stride;
+            st_dev(pg + 4 + tid, A);
+            if (tid == 0) {
+                st_dev(pg + 0, M);
+                st_dev(pg + 1, Ls);
+            }
+        }
+    }
+}
+
+// Combines the n_ch chunk partials of each of the G heads of one unit:
+//   y = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M),  M = max_c m_c.
+// The workgroup is cut into 8 groups of 32 threads; a group owns 4 output
+// channels per thread and walks its share of a head's chunks in ascending
+// order with a running (max, denominator, numerator) state; the groups of a
+// head are then combined in group order.  The schedule depends only on
+// (G, n_ch).  wait_chunk(cc, active) is called by every lane of a group before
+// the group reads chunk cc (a no-op when all partials are already complete).
+// red: LDS [8][kD], red_ml: LDS [8][2].  All 256 threads must call it.
+template <class Wait>
+__device__ __forceinline__ void merge_partials(const float *part_unit, int G, int n_ch, float *out_unit,
+                                               float (*red)[kD], float (*red_ml)[2], Wait wait_chunk)
+{
+    const int tid = threadIdx.x;
+    const int gph = (G >= 8) ? 1 : (G >= 4) ? 2 : (G >= 2) ? 4 : 8;  // groups per head
+    const int hpr = 8 / gph;                                          // heads per round
+    const int cl = tid >> 5, cg = tid & 31;
+    const int hr = cl / gph, sub = cl % gph;
+    for (int g0 = 0; g0 < G; g0 += hpr) {
+        const int g = g0 + hr;
+        float m = kNegInf, l = 0.0f;
+        float4 A = make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool active = g < G;
+        const float *ph = part_unit + (size_t)(active ? g : 0) * n_ch * kPartStride;
+        // every group runs the same number of batches so that wait_chunk stays wave-uniform
+        for (int c0 = sub; c0 - sub < n_ch; c0 += gph * 4) {
+            float2 ml[4];
+            float4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int cc = c0 + i * gph;
+                const bool have = active && cc < n_ch;
+                wait_chunk(cc, have);
+                if (have) {
+                    const float *pc = ph + (size_t)cc * kPartStride;
+                    ml[i] = ld_dev(reinterpret_cast<const float2 *>(pc));
+                    const float2 lo = ld_dev(reinterpret_cast<const float2 *>(pc + 4 + cg * 4));
+                    const float2 hi = ld_dev(reinterpret_cast<const float2 *>(pc + 6 + cg * 4));
+                    v[i] = make_float4(lo.x, lo.y, hi.x, hi.y);
+                } else {
+                    ml[i] = make_float2(kNegInf, 0.f);
+                    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (ml[i].x != kNegInf) {
+                    const float mn = fmaxf(m, ml[i].x);
+                    const float so = (m == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(m - mn);
+                    const float sn = __builtin_amdgcn_exp2f(ml[i].x - mn);
+                    l = l * so + ml[i].y * sn;
+                    A.x = A.x * so + v[i].x * sn;
+                    A.y = A.y * so + v[i].y * sn;
+                    A.z = A.z * so + v[i].z * sn;
+                    A.w = A.w * so + v[i].w * sn;
+                    m = mn;
+                }
+            }
+        }
+        *reinterpret_cast<float4 *>(&red[cl][cg * 4]) = A;
+        if (cg == 0) {
+            red_ml[cl][0] = m;
+            red_ml[cl][1] = l;
+        }
+        __syncthreads();
+        for (int hh = tid >> 7; hh < hpr; hh += 2) {
+            const int g2 = g0 + hh, cc = tid & (kD - 1);
+            if (g2 < G) {
+                float M = kNegInf;
+                for (int sgi = 0; sgi < gph; ++sgi) M = fmaxf(M, red_ml[hh * gph + sgi][0]);
+                float As = 0.0f, Ls = 0.0f;
+                for (int sgi = 0; sgi < gph; ++sgi) {
+                    const float ms = red_ml[hh * gph + sgi][0];
+                    const float f = (ms == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(ms - M);
+                    As += f * red[hh * gph + sgi][cc];
+                    Ls += f * red_ml[hh * gph + sgi][1];
+                }
+                out_unit[(size_t)g2 * kD + cc] = As / Ls;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace ds

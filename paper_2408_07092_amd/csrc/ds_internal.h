@@ -31,7 +31,11 @@ struct UnitCtl {
     uint32_t arrive_a;  // workgroups of the scoring kernel that finished this unit
     uint32_t arrive_b;  // same, candidate kernel
     uint32_t arrive_c;  // same, attention kernels
-    uint32_t pad[8];
+    uint32_t cnt_a;     // single-launch path: chunks scored / candidates written / partials written
+    uint32_t cnt_b;
+    uint32_t cnt_c;
+    uint32_t err;       // single-launch path: non-zero if a bounded wait gave up (stays set)
+    uint32_t pad[4];
 };
 static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte record");
 
@@ -46,6 +50,7 @@ enum KernelId {
     KID_LABEL,
     KID_GATHER_HOST,
     KID_PROBE,
+    KID_FUSED,
     KID_COUNT
 };
 
@@ -55,18 +60,27 @@ struct Plan {
     int sc_chunk, n_sc;  // tokens per workgroup / workgroups per unit, scoring
     int ch, n_ch;        // same for candidate collection, compaction and attention
     int key_stride;      // uint32 keys per unit (L rounded up to 4)
-    size_t off_ctl, off_hist, off_keys, off_cand, off_ndef, off_offs, off_part;
+    size_t off_ctl, off_hist, off_coarse, off_keys, off_cand, off_ndef, off_offs, off_part;
+    size_t off_fused;    // data region of the single-launch path (same control prefix)
     size_t total;
+};
+// Launch shape of the single-launch path, decided at launch time from the device's capacity.
+struct FusedPlan {
+    bool ok;
+    int P, n_svc, n_ch, items, max_items, rmode;
+    size_t lds;
 };
 // Plan of dense / gathered-rows attention (token chunks of dn_chunk).
 struct DensePlan {
     int units, G;
     int ch, n_ch;
-    size_t off_ctl, off_part, total;
+    size_t off_ctl, off_part, total;  // same control prefix as Plan
 };
 
 bool make_plan(const ds_shape_t &s, Plan *p);
 bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);
+bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f);
+size_t fused_workspace_bytes(const ds_shape_t &s, const Plan &p);
 
 // profiling hooks (ds_profile.cpp)
 void prof_begin(int id, hipStream_t st);
@@ -91,6 +105,9 @@ hipError_t launch_label(const void *K, const int32_t *channels, void *label, con
                         int t0, int n, hipStream_t st);
 hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,
                               const ds_shape_t &s, hipStream_t st);
+hipError_t launch_fused(const void *q, const void *label, const void *K, const void *V,
+                        const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
+                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
 
 int tune_get(int knob);

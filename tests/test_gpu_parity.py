@@ -15,6 +15,15 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["one_launch", "three_launch"], autouse=True)
+def decode_path(request):
+    """Every test runs on both implementations of ds_sparse_decode: the single
+    launch (workers + reducers) and the three-launch path."""
+    ds.ds_tune_set(3, 2 if request.param == "one_launch" else 1)
+    yield request.param
+    ds.ds_tune_set(3, 0)
+
+
 def rand_channels(Hkv, d, r, seed, sort=True):
     rng = np.random.default_rng(seed)
     rows = [rng.permutation(d)[:r] for _ in range(Hkv)]

@@ -40,13 +40,15 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     const int64_t tokens = (int64_t)p->units * s.L;
 
     int sc = g_tune[0];
-    if (sc == 0) sc = (tokens >= (1 << 20)) ? 2048 : 1024;
+    // fewer, larger workgroups: every workgroup pays an arrival atomic and a histogram flush
+    if (sc == 0) sc = (tokens >= (1 << 21)) ? 4096 : (tokens >= (1 << 20)) ? 2048 : 1024;
     p->sc_chunk = sc;
     p->n_sc = (s.L + sc - 1) / sc;
 
     int ch = g_tune[1];
     if (ch == 0) {
-        ch = (tokens >= (1 << 21)) ? 1024 : (tokens >= (1 << 20)) ? 512 : 256;
+        ch = (tokens >= (1 << 21)) ? 2048 : (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 512 : 256;
+        if (p->G >= 4 && ch < 4096) ch *= 2;  // a query group writes G partials per chunk
         while ((s.L + ch - 1) / ch > kMaxChunks && ch < 4096) ch *= 2;
     }
     p->ch = ch;

@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
     __shared__ uint32_t s_w[4], s_flag;
     __shared__ __attribute__((aligned(16))) float red[8][kD];
     __shared__ float red_ml[8][2];
-    __shared__ __attribute__((aligned(16))) _Float16 qsh[GT][kD];
+    __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
+    __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
     __shared__ __attribute__((aligned(16))) float wpart[4][GT][kPartStride];
 
     const int tid = threadIdx.x;
@@ -82,21 +83,33 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
         row_bytes = 2 * kD;
     }
 
+    auto row_of = [&](int ri) { return (MODE == 0) ? sel[ri] : (MODE == 1) ? (t0 + ri) : ri; };
     for (int g0 = 0; g0 < a.G; g0 += GT) {
+        float *po = a.part + (((size_t)u * a.G + g0) * a.n_ch + c) * kPartStride;
+        const _Float16 *q0 = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0) * kD;
         __syncthreads();
-        if (tid < GT * 16) {
-            const int g = tid >> 4, p = tid & 15;
-            const _Float16 *src = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0 + g) * kD + p * 8;
-            *reinterpret_cast<uint4 *>(&qsh[g][p * 8]) = *reinterpret_cast<const uint4 *>(src);
+        if constexpr (GT >= 4) {
+            // query group on the matrix cores: up to GT heads share every gathered row
+            const int n_heads = min(GT, a.G - g0);
+            half8 qreg[4];
+            load_q_mfma(q0, n_heads, qreg);
+            MfmaState st;
+            st.init();
+            attend_rows_mfma(Ku, Vu, row_bytes, n, row_of, qreg, st, sc_sh[tid >> 6]);
+            DS_TR(2);
+            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride);
+        } else {
+            if (tid < GT * 16) {
+                const int g = tid >> 4, p = tid & 15;
+                *reinterpret_cast<uint4 *>(&qsh[g][p * 8]) = *reinterpret_cast<const uint4 *>(q0 + (size_t)g * kD + p * 8);
+            }
+            __syncthreads();
+            RowState<GT> st;
+            st.init();
+            attend_rows<GT>(Ku, Vu, row_bytes, n, row_of, qsh, st);
+            DS_TR(2);
+            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride);
         }
-        __syncthreads();
-        RowState<GT> st;
-        st.init();
-        attend_rows<GT>(Ku, Vu, row_bytes, n,
-                        [&](int ri) { return (MODE == 0) ? sel[ri] : (MODE == 1) ? (t0 + ri) : ri; }, qsh, st);
-        DS_TR(2);
-        wg_store_partial<GT>(st, wpart, a.part + (((size_t)u * a.G + g0) * a.n_ch + c) * kPartStride,
-                             (size_t)a.n_ch * kPartStride);
     }
 
     // ---- last workgroup of the unit: combine the chunk partials of every head of the group
@@ -115,18 +128,21 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // ---------------------------------------------------------------- launchers
 static inline char *wsp(void *ws, size_t off) { return static_cast<char *>(ws) + off; }
 
+// Heads handled per pass over the rows: 1 or 2 on the vector ALUs, 4 / 8 / 16 (padded) on the
+// matrix cores; larger groups take several passes of 16.
 static int pick_gt(int G)
 {
-    if (G % 8 == 0) return 8;
-    if (G % 4 == 0) return 4;
-    if (G % 2 == 0) return 2;
-    return 1;
+    if (G <= 2) return G;
+    if (G <= 4) return 4;
+    if (G <= 8) return 8;
+    return 16;
 }
 
 template <int MODE>
 static void launch_attend_mode(const AttendArgs &a, dim3 grid, size_t shmem, hipStream_t st)
 {
     switch (pick_gt(a.G)) {
+    case 16: hipLaunchKernelGGL((k_attend<16, MODE>), grid, dim3(kWG), shmem, st, a); break;
     case 8: hipLaunchKernelGGL((k_attend<8, MODE>), grid, dim3(kWG), shmem, st, a); break;
     case 4: hipLaunchKernelGGL((k_attend<4, MODE>), grid, dim3(kWG), shmem, st, a); break;
     case 2: hipLaunchKernelGGL((k_attend<2, MODE>), grid, dim3(kWG), shmem, st, a); break;

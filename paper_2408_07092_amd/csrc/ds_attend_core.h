@@ -16,7 +16,6 @@ namespace ds {
 
 constexpr float kScaleLog2 = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
 
-__device__ __forceinline__ float dpp_add(float v, float moved) { return v + moved; }
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
 {
@@ -117,17 +116,50 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
     }
 }
 
+// Second half of a workgroup's partial: the four wavefronts' states in
+// wpart[wave][head] = {m, l, -, -, acc[128]} (LDS) are merged in wave order and
+// written as one partial per head to po + g * head_stride with device-scope
+// stores.  Starts with a barrier; callers put a barrier between two uses of wpart.
+template <int GH>
+__device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride], int n_heads, float *po,
+                                                 size_t head_stride)
+{
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if (tid < kD) {
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+            if (g < n_heads) {
+                float M = kNegInf;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][g][0]);
+                float A = 0.0f, Ls = 0.0f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float mw = wpart[w][g][0];
+                    const float f = (mw == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(mw - M);
+                    A += f * wpart[w][g][4 + tid];
+                    Ls += f * wpart[w][g][1];
+                }
+                float *pg = po + (size_t)g * head_stride;
+                st_dev(pg + 4 + tid, A);
+                if (tid == 0) {
+                    st_dev(pg + 0, M);
+                    st_dev(pg + 1, Ls);
+                }
+            }
+        }
+    }
+}
+
 // Merges the 16 slot states of the workgroup (4 slots per wave in slot order,
-// then the 4 waves in wave order) and writes one partial {m, l, -, -, acc[128]}
-// per head g to po + g * head_stride with device-scope stores.
-// wpart: LDS [4][GT][kPartStride].  Contains one barrier; callers must put a
-// barrier between two uses of wpart.
+// then the 4 waves in wave order) and writes one partial per head.
 template <int GT>
 __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
                                                  float (*wpart)[GT][kPartStride], float *po,
                                                  size_t head_stride)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
@@ -153,29 +185,131 @@ __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
             }
         }
     }
-    __syncthreads();
-    if (tid < kD) {
+    wg_combine_store<GT>(wpart, GT, po, head_stride);
+}
+
+// ---------------------------------------------------------------- matrix-core path for query groups
+// When several query heads share a KV head, scores and P.V are small dense
+// contractions over the gathered rows: S[token][head] = K[token,:] . q[head,:]
+// (16 tokens x up to 16 heads x 128 channels, fp16 MFMA 16x16x16) and
+// O[head][channel] += P[token][head] * V[token][channel] (fp32 MFMA 16x16x4, P
+// and V exact in binary32).  A wavefront owns tiles of 16 rows.
+//
+// Lane roles (l = lane, lo = l % 16, hi = l / 16):
+//   K operand   : token lo of the tile, 16-byte pieces at channels 8*(4x + hi), x = 0..3
+//   q operand   : head lo, the same channel pieces (loaded once per item)
+//   S result    : head lo, tokens 4*hi + r, r = 0..3   -> softmax state per lane for head lo
+//   V operand   : token 4*hi + r, channels 8*lo .. 8*lo+7 (the whole 256-byte row per 16 lanes)
+//   O result e  : heads 4*hi + rr, channel 8*lo + e     (8 accumulators of 4 values)
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+struct MfmaState {
+    float m, l;       // running max / partial denominator of head lo over this lane's tokens
+    float4v O[8];     // O[e][rr]: head 4*hi + rr, channel 8*lo + e
+    __device__ __forceinline__ void init()
+    {
+        m = kNegInf;
+        l = 0.0f;
 #pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float M = kNegInf;
+        for (int e = 0; e < 8; ++e) O[e] = (float4v){0.f, 0.f, 0.f, 0.f};
+    }
+};
+
+// q rows of the heads [g0, g0 + 16) of a unit as MFMA operands (zeros beyond n_heads).
+__device__ __forceinline__ void load_q_mfma(const _Float16 *q_unit, int n_heads, half8 (&qreg)[4])
+{
+    const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][g][0]);
-            float A = 0.0f, Ls = 0.0f;
+    for (int x = 0; x < 4; ++x) {
+        qreg[x] = (half8)(_Float16)0;
+        if (lo < n_heads) qreg[x] = *reinterpret_cast<const half8 *>(q_unit + (size_t)lo * kD + 8 * (4 * x + hi));
+    }
+}
+
+// sc_lds: 16 floats of LDS private to the calling wavefront.
+template <class RowOf>
+__device__ __forceinline__ void attend_rows_mfma(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
+                                                 RowOf row_of, const half8 (&qreg)[4], MfmaState &st,
+                                                 float *sc_lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lo = lane & 15, hi = lane >> 4;
+    for (int r0 = wave * 16; r0 < n; r0 += 64) {
+        // the eight 16-byte loads of the tile are issued before the first use; rows past the end
+        // re-read the last row of the list (in bounds) and their scores are masked
+        half8 kr[4], vr[4];
+        const uint32_t krow = (uint32_t)row_of(min(r0 + lo, n - 1)) * row_bytes;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float mw = wpart[w][g][0];
-                const float f = (mw == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(mw - M);
-                A += f * wpart[w][g][4 + tid];
-                Ls += f * wpart[w][g][1];
+        for (int x = 0; x < 4; ++x)
+            kr[x] = *reinterpret_cast<const half8 *>(Ku + krow + 16u * (uint32_t)(4 * x + hi));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t vrow = (uint32_t)row_of(min(r0 + 4 * hi + r, n - 1)) * row_bytes;
+            vr[r] = *reinterpret_cast<const half8 *>(Vu + vrow + 16u * (uint32_t)lo);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float4v S = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const half4v ka = {kr[x][4 * y], kr[x][4 * y + 1], kr[x][4 * y + 2], kr[x][4 * y + 3]};
+                const half4v qb = {qreg[x][4 * y], qreg[x][4 * y + 1], qreg[x][4 * y + 2], qreg[x][4 * y + 3]};
+                S = __builtin_amdgcn_mfma_f32_16x16x16f16(ka, qb, S, 0, 0, 0);
             }
-            float *pg = po + (size_t)g * head_stride;
-            st_dev(pg + 4 + tid, A);
-            if (tid == 0) {
-                st_dev(pg + 0, M);
-                st_dev(pg + 1, Ls);
-            }
+        float s[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s[r] = (r0 + 4 * hi + r < n) ? S[r] * kScaleLog2 : kNegInf;
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));  // over the 16 tokens of the tile, per head (token r0 is valid)
+        const float mn = fmaxf(st.m, mx);
+        const float sc = (st.m == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m - mn);
+        st.m = mn;
+        float p[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] - mn);
+        st.l = st.l * sc + ((p[0] + p[1]) + (p[2] + p[3]));
+        if (__any(sc != 1.0f)) {
+            // the accumulators of heads 4*hi .. 4*hi+3 live in this lane; their scale factors sit in
+            // lanes 4*hi .. 4*hi+3 of the wavefront: pass them through the wavefront's LDS words
+            if (hi == 0) sc_lds[lo] = sc;
+            const float4v f = *reinterpret_cast<const float4v *>(sc_lds + 4 * hi);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.O[e] *= f;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.O[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[r], (float)vr[r][e], st.O[e], 0, 0, 0);
+    }
+}
+
+// Writes the calling wavefront's state to wpart[wave][head] and runs the workgroup combine.
+template <int GH>
+__device__ __forceinline__ void wg_store_partial_mfma(const MfmaState &st, float (*wpart)[GH][kPartStride],
+                                                      int n_heads, float *po, size_t head_stride)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lo = lane & 15, hi = lane >> 4;
+    float lv = st.l;
+    lv += __shfl_xor(lv, 16);
+    lv += __shfl_xor(lv, 32);
+    if (hi == 0 && lo < n_heads) {
+        wpart[wave][lo][0] = st.m;
+        wpart[wave][lo][1] = lv;
+    }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int head = 4 * hi + rr;
+        if (head < n_heads) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) wpart[wave][head][4 + 8 * lo + e] = st.O[e][rr];
         }
     }
+    wg_combine_store<GH>(wpart, n_heads, po, head_stride);
 }
 
 // Combines the n_ch chunk partials of each of the G heads of one unit:

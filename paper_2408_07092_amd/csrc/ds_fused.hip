@@ -102,6 +102,7 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
     constexpr int NV = (RMODE > 0) ? RMODE / 8 : 1;
     constexpr int TPT = kItemTokens / kWG;
     __shared__ uint32_t s_bstar[kMaxItems], s_rdy[1], s_val[1][2], s_w[4];
+    __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
 
     uint32_t *hist16 = reinterpret_cast<uint32_t *>(smem);                    // 2048 words, 2 bins each
     uint32_t *keys = hist16 + kHistBins / 2;                                   // max_items * 1024
@@ -320,9 +321,24 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
         const char *Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
         const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
         const _Float16(*qj)[kD] = reinterpret_cast<const _Float16(*)[kD]>(qsh + (size_t)j * GT * kD);
-        RowState<GT> st;
-        st.init();
-        attend_rows<GT>(Ku, Vu, 2 * kD, (int)n_def, [&](int ri) { return sel[ri]; }, qj, st);
+        // query groups of 4 or 8 heads run on the matrix cores, 1 or 2 heads on the vector ALUs
+        RowState<(GT >= 4 ? 1 : GT)> stv;
+        MfmaState stm;
+        half8 qreg[4];
+        if constexpr (GT >= 4) {
+            load_q_mfma(qsh + (size_t)j * GT * kD, GT, qreg);
+            stm.init();
+        } else {
+            stv.init();
+        }
+        auto attend = [&](const int *list, int n_rows) {
+            if constexpr (GT >= 4)
+                attend_rows_mfma(Ku, Vu, 2 * kD, n_rows, [&](int ri) { return list[ri]; }, qreg, stm,
+                                 sc_sh[tid >> 6]);
+            else
+                attend_rows<GT>(Ku, Vu, 2 * kD, n_rows, [&](int ri) { return list[ri]; }, qj, stv);
+        };
+        attend(sel, (int)n_def);
 
         if (tid == 0) {
             s_rdy[0] = spin_equals(&a.ctl[u].arrive_b, 1u, a.spin_limit) ? 1u : 0u;
@@ -356,9 +372,10 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
                 if (fs[e]) csel[ps++] = tok[e];
             __syncthreads();
         }
-        attend_rows<GT>(Ku, Vu, 2 * kD, (int)n_csel, [&](int ri) { return csel[ri]; }, qj, st);
-        wg_store_partial<GT>(st, wpart, a.part + (((size_t)u * a.G) * a.n_ch + c) * kPartStride,
-                             (size_t)a.n_ch * kPartStride);
+        attend(csel, (int)n_csel);
+        float *po = a.part + (((size_t)u * a.G) * a.n_ch + c) * kPartStride;
+        if constexpr (GT >= 4) wg_store_partial_mfma<GT>(stm, wpart, GT, po, (size_t)a.n_ch * kPartStride);
+        else wg_store_partial<GT>(stv, wpart, po, (size_t)a.n_ch * kPartStride);
         if (a.idx_out) {
             // the caller's index list is ascending over all selected tokens of the unit
             __syncthreads();

@@ -192,7 +192,9 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
  *   knob 3: how ds_sparse_decode is launched: 0 = automatic, 1 = three launches
  *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
- *           workgroups when the shape and the device allow it (else three launches)
+ *           workgroups when the shape and the device allow it (else three launches),
+ *           3 = two launches: that co-resident launch up to the threshold candidates, then
+ *           one attention launch in which every workgroup settles its unit's exact threshold
  * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
  * changing a knob changes ds_workspace_bytes() and the workspace layout, so
  * re-query the size and clear the workspace again afterwards.

@@ -97,7 +97,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 // ---------------------------------------------------------------- per-kernel event timing
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
-    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused"};
+    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -298,7 +298,8 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
     hipStream_t st = (hipStream_t)stream;
     FusedPlan f;
     if (make_fused_plan(*shape, p, &f)) {
-        DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
+        if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
+        else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
     }
     rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st);
@@ -428,7 +429,7 @@ ds_status_t ds_tune_set(int knob, int value)
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 1 && (value % 256 != 0 || value > 4096)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 3 && value > 2) return DS_ERR_SHAPE;
+        if (knob == 3 && value > 3) return DS_ERR_SHAPE;
     }
     g_tune[knob] = value;
     return DS_OK;

@@ -47,11 +47,13 @@ struct FusedArgs {
     uint32_t *ncd, *ndef;  // [items] candidates / keys above b* of each chunk
     uint32_t *offs;        // [items] offset of the chunk in the ascending index list
     uint2 *mb_cand;        // [items][1024] (key, token)
+    uint16_t *deflist;     // [items][1024] tokens above b* (offset in the chunk), two-launch mode
     float *part;           // [units * G][n_ch][kPartStride]
     float *out;
     int32_t *idx_out;
     int Hq, Hkv, G, L, L_max, r, k, k_eff;
     int units, n_ch, items, P, n_svc, max_items;
+    int two_launch;        // 1: stop after the candidate phase; k_attend2 finishes the call
     uint32_t spin_limit;
 };
 
@@ -268,7 +270,7 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
             kc += fc[e] ? 1u : 0u;
         }
         uint32_t n_def, n_cand;
-        (void)block_exclusive_scan(kd, s_w, &n_def);
+        uint32_t pd = block_exclusive_scan(kd, s_w, &n_def);
         uint32_t pc = block_exclusive_scan(kc, s_w, &n_cand);
         uint2 *mb = a.mb_cand + (size_t)i * kItemTokens;
 #pragma unroll
@@ -278,10 +280,21 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
             st_dev(a.ncd + i, n_cand);
             st_dev(a.ndef + i, n_def);
         }
+        if (a.two_launch) {
+            // the attention launch reads the tokens above b* as a list (ascending)
+            uint16_t *dl = a.deflist + (size_t)i * kItemTokens;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = t0 + tid * 4 + e;
+                if (t < t1 && (kj[tid * 4 + e] >> kKeyShift) > bstar) dl[pd++] = (uint16_t)(tid * 4 + e);
+            }
+            continue;
+        }
         wait_stores();
         __syncthreads();
         if (tid == 0) bump(&a.ctl[u].cnt_b);
     }
+    if (a.two_launch) return;
     DS_TR(4);
 
     // ---- phase A, item by item.  The tokens above the threshold bin are certainly selected:
@@ -458,6 +471,7 @@ __device__ __forceinline__ void fused_reducer(const FusedArgs &a, char *smem, in
         __syncthreads();
     }
     DS_TR(9);
+    if (a.two_launch) return;
 
     // ---- step B: exact k-th key T among the candidates, tie cut, index-list offsets
     for (int u = s; u < a.units; u += a.n_svc) {
@@ -601,6 +615,215 @@ __global__ __launch_bounds__(kWG) void k_fused(FusedArgs a)
     else fused_worker<GT, RMODE>(a, smem, (int)blockIdx.x - a.n_svc);
 }
 
+// ---------------------------------------------------------------- second launch of the two-launch path
+// After k_fused stopped behind the candidate phase, every unit has its threshold bin b*, and
+// every chunk its list of tokens above b*, its candidates (keys in b*) and their counts.
+// Each workgroup of this launch settles the exact threshold for its unit itself -- all
+// candidates of the unit (about 1-2 % of its tokens) go to LDS and are radix-selected there;
+// doing that in each workgroup costs less than a hand-over between workgroups -- and then
+// gathers and attends its own chunks: tokens above b* first, then its selected candidates.
+struct Attend2Args {
+    const _Float16 *q, *K, *V;
+    UnitCtl *ctl;
+    const uint32_t *ncd, *ndef;
+    const uint2 *mb_cand;
+    const uint16_t *deflist;
+    float *part, *out;
+    int32_t *idx_out;
+    int Hq, Hkv, G, L, L_max, k, k_eff, n_ch, m, n_wg;
+};
+
+template <int GT>
+__global__ __launch_bounds__(kWG) void k_attend2(Attend2Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ uint32_t s_w[4], s_res[2], s_flag;
+    __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
+    __shared__ __attribute__((aligned(16))) float red[8][kD];
+    __shared__ float red_ml[8][2];
+    uint32_t *lh = reinterpret_cast<uint32_t *>(smem);                     // 2048 words
+    uint2 *cl = reinterpret_cast<uint2 *>(lh + 2048);                      // kCandLds entries
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(cl + kCandLds);           // n_ch: selected per chunk
+    uint32_t *ncs = cnt + ((a.n_ch + 3) & ~3);                             // n_ch: candidates per chunk
+    int *sel = reinterpret_cast<int *>(ncs + ((a.n_ch + 3) & ~3));         // m * 1024 rows
+    _Float16 *qsh = reinterpret_cast<_Float16 *>(sel + (size_t)a.m * kItemTokens);  // GT rows
+    float(*wpart)[GT][kPartStride] = reinterpret_cast<float(*)[GT][kPartStride]>(qsh + GT * kD);
+
+    const int tid = threadIdx.x;
+    const int u = blockIdx.y, cw = blockIdx.x;
+    const int b = u / a.Hkv, h = u % a.Hkv;
+    const int c_lo = cw * a.m, c_hi = min(a.n_ch, c_lo + a.m);
+    const uint32_t bstar = a.ctl[u].bstar;
+    uint32_t krem = a.ctl[u].krem;
+
+    if (GT < 4 && tid < GT * 16) {
+        const int g = tid >> 4, p = tid & 15;
+        const _Float16 *src = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g) * kD + p * 8;
+        *reinterpret_cast<uint4 *>(&qsh[g * kD + p * 8]) = *reinterpret_cast<const uint4 *>(src);
+    }
+
+    // ---- all candidates of the unit -> LDS: four threads per chunk fetch the chunk's counts and
+    // its first 16 candidates in one round trip; the rest (rare) follows
+    uint32_t n = 0;
+    for (int cbase = 0; cbase < a.n_ch; cbase += kWG / 4) {
+        const int c = cbase + (tid >> 2), sub = tid & 3;
+        const bool live = c < a.n_ch;
+        const size_t i = (size_t)u * a.n_ch + (live ? c : 0);
+        const uint32_t nc = live ? a.ncd[i] : 0u;
+        const uint32_t nd = live ? a.ndef[i] : 0u;
+        const uint2 *mb = a.mb_cand + i * kItemTokens;
+        uint2 e[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) e[x] = mb[sub + 4 * x];
+        if (live && sub == 0) {
+            cnt[c] = nd;
+            ncs[c] = nc;
+        }
+        const uint32_t mine = nc > (uint32_t)sub ? (nc - sub + 3) / 4 : 0u;
+        uint32_t total;
+        uint32_t at = n + block_exclusive_scan(mine, s_w, &total);
+        n += total;
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if ((uint32_t)x < mine && at + x < (uint32_t)kCandLds) cl[at + x] = e[x];
+        for (uint32_t x = 4; x < mine; ++x) {
+            const uint2 ex = mb[sub + 4 * x];
+            if (at + x < (uint32_t)kCandLds) cl[at + x] = ex;
+        }
+    }
+    const bool in_lds = n <= (uint32_t)kCandLds;
+    __syncthreads();
+    auto each = [&](auto f) {
+        if (in_lds) {
+            for (uint32_t i = tid; i < n; i += kWG) f(cl[i]);
+        } else {
+            for (int c = 0; c < a.n_ch; ++c) {
+                const uint2 *mb = a.mb_cand + ((size_t)u * a.n_ch + c) * kItemTokens;
+                for (uint32_t e = tid; e < ncs[c]; e += kWG) f(mb[e]);
+            }
+        }
+    };
+    // ---- exact k-th key T (10 + 10 key bits), ties towards the lowest token index
+    svc_radix_pass<4, true>(each, [](uint2) { return true; },
+                            [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
+    const uint32_t pre22 = (bstar << 10) | s_res[0];
+    krem = s_res[1];
+    __syncthreads();
+    svc_radix_pass<4, true>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
+                            [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
+    const uint32_t T = (pre22 << 10) | s_res[0];
+    const uint32_t m_ties = s_res[1];
+    const uint32_t n_ties = lh[s_res[0]];
+    __syncthreads();
+    int tcut = 0x7fffffff;
+    if (m_ties < n_ties) {
+        svc_radix_pass<8, false>(each, [&](uint2 e) { return e.x == T; },
+                                 [](uint2 e) { return e.y >> 20; }, m_ties, lh, s_w, s_res);
+        uint32_t prefix = s_res[0], want = s_res[1];
+        __syncthreads();
+        svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+                                 [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
+        prefix = (prefix << 10) | s_res[0];
+        want = s_res[1];
+        __syncthreads();
+        svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+                                 [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
+        tcut = (int)((prefix << 10) | s_res[0]);
+        __syncthreads();
+    }
+
+    // ---- rows of my chunks: tokens above b* (ascending), then the chunk's selected candidates
+    int n_rows = 0;
+    for (int c = c_lo; c < c_hi; ++c) {
+        const size_t i = (size_t)u * a.n_ch + c;
+        const int t0 = c * kItemTokens;
+        const int nd = (int)a.ndef[i];
+        const uint16_t *dl = a.deflist + i * kItemTokens;
+        for (int x = tid; x < nd; x += kWG) sel[n_rows + x] = t0 + dl[x];
+        n_rows += nd;
+        const uint2 *mb = a.mb_cand + i * kItemTokens;
+        const uint32_t nc = ncs[c];
+        for (uint32_t x0 = 0; x0 < nc; x0 += kWG) {
+            const uint32_t x = x0 + tid;
+            uint2 e = make_uint2(0u, 0u);
+            if (x < nc) e = mb[x];
+            const bool f = x < nc && is_selected(e.x, (int)e.y, T, tcut);
+            uint32_t total;
+            const uint32_t at = block_exclusive_scan(f ? 1u : 0u, s_w, &total);
+            if (f) sel[n_rows + at] = (int)e.y;
+            n_rows += (int)total;
+        }
+    }
+    __syncthreads();
+
+    if (a.idx_out) {
+        // ascending index list: per-chunk counts -> offsets; my chunks merge their two lists via flags
+        each([&](uint2 e) {
+            if (is_selected(e.x, (int)e.y, T, tcut)) atomicAdd(&cnt[e.y / (uint32_t)kItemTokens], 1u);
+        });
+        __syncthreads();
+        uint32_t *flags = lh;  // 1024 words
+        int32_t *io = a.idx_out + (size_t)u * a.k;
+        for (int c = c_lo; c < c_hi; ++c) {
+            uint32_t off = 0;
+            for (int cc = tid; cc < c; cc += kWG) off += cnt[cc];
+            uint32_t tot_off;
+            (void)block_exclusive_scan(off, s_w, &tot_off);
+            for (int x = tid; x < kItemTokens; x += kWG) flags[x] = 0u;
+            __syncthreads();
+            const size_t i = (size_t)u * a.n_ch + c;
+            const int nd = (int)a.ndef[i];
+            const uint16_t *dl = a.deflist + i * kItemTokens;
+            for (int x = tid; x < nd; x += kWG) flags[dl[x]] = 1u;
+            const uint2 *mb = a.mb_cand + i * kItemTokens;
+            for (uint32_t x = tid; x < ncs[c]; x += kWG) {
+                const uint2 e = mb[x];
+                if (is_selected(e.x, (int)e.y, T, tcut)) flags[e.y - (uint32_t)(c * kItemTokens)] = 1u;
+            }
+            __syncthreads();
+            uint32_t mine = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine += flags[tid * 4 + e];
+            uint32_t total;
+            uint32_t at = tot_off + block_exclusive_scan(mine, s_w, &total);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (flags[tid * 4 + e] && at < (uint32_t)a.k_eff) io[at++] = c * kItemTokens + tid * 4 + e;
+            __syncthreads();
+        }
+        if (cw == 0)
+            for (int x = a.k_eff + tid; x < a.k; x += kWG) io[x] = -1;
+    }
+
+    // ---- gather + attention over my rows, one partial per head
+    const char *Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
+    const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
+    float *po = a.part + (((size_t)u * a.G) * a.n_wg + cw) * kPartStride;
+    if constexpr (GT >= 4) {
+        half8 qreg[4];
+        load_q_mfma(a.q + ((size_t)b * a.Hq + (size_t)h * a.G) * kD, a.G, qreg);
+        MfmaState st;
+        st.init();
+        attend_rows_mfma(Ku, Vu, 2 * kD, n_rows, [&](int ri) { return sel[ri]; }, qreg, st, sc_sh[tid >> 6]);
+        wg_store_partial_mfma<GT>(st, wpart, a.G, po, (size_t)a.n_wg * kPartStride);
+    } else {
+        RowState<GT> st;
+        st.init();
+        attend_rows<GT>(Ku, Vu, 2 * kD, n_rows, [&](int ri) { return sel[ri]; },
+                        reinterpret_cast<const _Float16(*)[kD]>(qsh), st);
+        wg_store_partial<GT>(st, wpart, po, (size_t)a.n_wg * kPartStride);
+    }
+
+    // ---- last workgroup of the unit: merge the partials, leave the unit's words clean
+    if (!last_arrival(&a.ctl[u].arrive_c, gridDim.x, &s_flag)) return;
+    if (tid == 0) {
+        a.ctl[u].arrive_c = 0u;
+        a.ctl[u].arrive_a = 0u;
+    }
+    merge_partials(a.part + (size_t)u * a.G * a.n_wg * kPartStride, a.G, a.n_wg,
+                   a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
+}
+
 // ---------------------------------------------------------------- host side
 static size_t worker_lds(int max_items, int GT, int rq)
 {
@@ -644,7 +867,7 @@ static bool compute_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f)
 bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f)
 {
     f->ok = false;
-    if (tune_get(3) != 2) return false;  // the single launch is opt-in (knob 3 = 2)
+    if (tune_get(3) != 2 && tune_get(3) != 3) return false;  // opt-in: knob 3 = 2 (one launch) or 3 (two)
     const int n_ch = (s.L + kItemTokens - 1) / kItemTokens;
     const int rmode = (s.r == 8) ? 8 : (s.r == 16) ? 16 : -1;
     std::lock_guard<std::mutex> lk(g_fused_mu);
@@ -700,7 +923,7 @@ static bool compute_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f)
 
 hipError_t launch_fused(const void *q, const void *label, const void *K, const void *V,
                         const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
-                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st)
+                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st, int two_launch)
 {
     char *base = static_cast<char *>(ws);
     FusedArgs a{};
@@ -717,6 +940,8 @@ hipError_t launch_fused(const void *q, const void *label, const void *K, const v
     a.offs = a.ndef + f.items;
     a.mb_cand = reinterpret_cast<uint2 *>(a.offs + f.items + (f.items & 1));
     a.part = reinterpret_cast<float *>(a.mb_cand + (size_t)f.items * kItemTokens);
+    a.deflist = reinterpret_cast<uint16_t *>(a.part + (size_t)p.units * p.G * f.n_ch * kPartStride);
+    a.two_launch = two_launch;
     a.out = out;
     a.idx_out = idx_out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max; a.r = s.r; a.k = s.k;
@@ -732,11 +957,63 @@ hipError_t launch_fused(const void *q, const void *label, const void *K, const v
     return e != hipSuccess ? e : hipGetLastError();
 }
 
+template <int GT>
+static void launch_attend2_gt(const Attend2Args &a, dim3 grid, size_t lds, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_attend2<GT>), grid, dim3(kWG), lds, st, a);
+}
+
+hipError_t launch_two(const void *q, const void *label, const void *K, const void *V,
+                      const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
+                      const FusedPlan &f, const ds_shape_t &s, hipStream_t st)
+{
+    hipError_t e = launch_fused(q, label, K, V, channels, ws, out, idx_out, p, f, s, st, 1);
+    if (e != hipSuccess) return e;
+    char *base = static_cast<char *>(ws);
+    Attend2Args a{};
+    a.q = static_cast<const _Float16 *>(q);
+    a.K = static_cast<const _Float16 *>(K);
+    a.V = static_cast<const _Float16 *>(V);
+    a.ctl = reinterpret_cast<UnitCtl *>(base + p.off_ctl);
+    uint32_t *ncd = reinterpret_cast<uint32_t *>(base + p.off_fused);
+    a.ncd = ncd;
+    a.ndef = ncd + f.items;
+    uint32_t *offs = ncd + 2 * (size_t)f.items;
+    a.mb_cand = reinterpret_cast<const uint2 *>(offs + f.items + (f.items & 1));
+    float *part = reinterpret_cast<float *>(const_cast<uint2 *>(a.mb_cand) + (size_t)f.items * kItemTokens);
+    a.part = part;
+    a.deflist = reinterpret_cast<const uint16_t *>(part + (size_t)p.units * p.G * f.n_ch * kPartStride);
+    a.out = out;
+    a.idx_out = idx_out;
+    a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max; a.k = s.k; a.k_eff = p.k_eff;
+    a.n_ch = f.n_ch;
+    // chunks per workgroup: about 2048 workgroups for single heads, larger tiles for query groups
+    int m = (int)(((long long)p.units * f.n_ch + 2047) / 2048);
+    if (p.G >= 4) m *= 2;
+    m = std::max(1, std::min(m, 4));
+    a.m = m;
+    a.n_wg = (f.n_ch + m - 1) / m;
+    const int gt = p.G;  // 1, 2, 4 or 8 (checked by the plan)
+    const size_t lds = (size_t)2048 * 4 + (size_t)kCandLds * 8 + (size_t)((f.n_ch + 3) & ~3) * 8 + (size_t)m * kItemTokens * 4 + (size_t)gt * kD * 2 +
+                       (size_t)4 * gt * kPartStride * 4;
+    const dim3 grid(a.n_wg, p.units);
+    prof_begin(KID_ATTEND2, st);
+    switch (gt) {
+    case 8: launch_attend2_gt<8>(a, grid, lds, st); break;
+    case 4: launch_attend2_gt<4>(a, grid, lds, st); break;
+    case 2: launch_attend2_gt<2>(a, grid, lds, st); break;
+    default: launch_attend2_gt<1>(a, grid, lds, st); break;
+    }
+    prof_end(KID_ATTEND2, st);
+    return hipGetLastError();
+}
+
 size_t fused_workspace_bytes(const ds_shape_t &s, const Plan &p)
 {
     const int n_ch = (s.L + kItemTokens - 1) / kItemTokens;
     const size_t items = (size_t)p.units * n_ch;
-    return items * 4 * 3 + 8 + items * kItemTokens * 8 + (size_t)p.units * p.G * n_ch * kPartStride * 4 + 256;
+    return items * 4 * 3 + 8 + items * kItemTokens * 8 + (size_t)p.units * p.G * n_ch * kPartStride * 4 +
+           items * kItemTokens * 2 + 256;
 }
 
 }  // namespace ds

@@ -51,6 +51,7 @@ enum KernelId {
     KID_GATHER_HOST,
     KID_PROBE,
     KID_FUSED,
+    KID_ATTEND2,
     KID_COUNT
 };
 
@@ -107,7 +108,10 @@ hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx
                               const ds_shape_t &s, hipStream_t st);
 hipError_t launch_fused(const void *q, const void *label, const void *K, const void *V,
                         const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
-                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st);
+                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st, int two_launch);
+hipError_t launch_two(const void *q, const void *label, const void *K, const void *V,
+                      const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
+                      const FusedPlan &f, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
 
 int tune_get(int knob);

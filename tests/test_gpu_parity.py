@@ -15,11 +15,11 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "three_launch"], autouse=True)
+@pytest.fixture(params=["one_launch", "two_launch", "three_launch"], autouse=True)
 def decode_path(request):
     """Every test runs on both implementations of ds_sparse_decode: the single
-    launch (workers + reducers) and the three-launch path."""
-    ds.ds_tune_set(3, 2 if request.param == "one_launch" else 1)
+    launch (workers + reducers), the two-launch and the three-launch path."""
+    ds.ds_tune_set(3, {"one_launch": 2, "two_launch": 3, "three_launch": 1}[request.param])
     yield request.param
     ds.ds_tune_set(3, 0)
 

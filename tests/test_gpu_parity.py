@@ -194,6 +194,34 @@ def test_select_gather_from_pinned_host_attend_rows():
     check_output(out.cpu().numpy(), ref_out, "offload split path")
 
 
+def test_offload_pipeline_double_buffer_matches_oracle_over_layers():
+    """Five layers through the two-slot pipeline (select / host-row fetch / attend on
+    three streams), twice, against the oracle per layer."""
+    from paper_2408_07092_amd.offload import OffloadDecoder
+    w = small_workload(2, 4, 2, 2500, 8, 150)          # GQA group 2, ragged L
+    shp = ds.shape(w.B, w.Hq, w.Hkv, w.d, w.L, w.L, w.r, w.k)
+    layers, outs, refs = [], [], []
+    for l in range(5):
+        t = make_layer_numpy(w, layer=l)
+        ch = rand_channels(w.Hkv, 128, 8, 100 + l)
+        lab_ref = O.build_label(t["K"], ch, w.L)
+        refs.append(O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, w.L, w.k, precision=32)[0])
+        layers.append((to_dev(t["q"]), to_dev(lab_ref), to_dev(ch),
+                       torch.from_numpy(t["K"]).pin_memory(), torch.from_numpy(t["V"]).pin_memory()))
+        outs.append(torch.zeros((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda"))
+    dec = OffloadDecoder(shp)
+    first = None
+    for rep in range(2):
+        dec.decode(layers, outs)
+        torch.cuda.synchronize()
+        got = [o.cpu().numpy() for o in outs]
+        for l in range(5):
+            check_output(got[l], refs[l], f"offload pipeline layer {l}")
+        blob = b"".join(g.tobytes() for g in got)
+        first = first or blob
+        assert blob == first
+
+
 # ---------------------------------------------------------------- calibration feeds the path
 def test_calibrated_channels_drive_selection_c1():
     w = WORKLOADS["C1"]

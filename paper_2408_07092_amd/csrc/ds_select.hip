@@ -52,12 +52,13 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                                                const _Float16 *__restrict__ label,
                                                const int32_t *__restrict__ channels,
                                                uint32_t *__restrict__ keys, uint32_t *hist,
-                                               UnitCtl *ctl, int Hq, int Hkv, int G, int L, int L_max,
+                                               uint32_t *coarse, UnitCtl *ctl, int Hq, int Hkv, int G, int L, int L_max,
                                                int r, int key_stride, int sc_chunk, int k_eff)
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ float qs_sh[kD];
-    __shared__ uint32_t s_w[4], s_res[2], s_flag;
+    __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
+    __shared__ uint32_t s_w[4], s_res[2], s_flag, s_fine[16];
     const int tid = threadIdx.x;
     const int u = blockIdx.y, b = u / Hkv, h = u % Hkv;
     const int t_begin = blockIdx.x * sc_chunk;
@@ -81,27 +82,33 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
         }
     };
     DS_TR(0);
-    // Label query of the group: sum over its heads (g ascending) of q_g[C[j]].  Threads
-    // [128, 128 + r) fetch it; the two dependent loads (channel id, then q) are started
-    // before the label loads so that they complete first, the rest of the sum follows.
-    const int j_q = tid - 128;
-    const bool has_q = j_q >= 0 && j_q < r;
+    // Label query of the group: sum over its heads (g ascending) of q_g[C[j]].  The channel
+    // ids and whole query rows (up to 8 heads at a time) are requested together with the first
+    // label rows -- one memory round trip instead of two dependent ones -- and the r values are
+    // then picked out of LDS.
     int c_q = 0;
-    _Float16 q0 = (_Float16)0;
-    if (has_q) {
-        c_q = channels[h * r + j_q];
-        q0 = q[((size_t)b * Hq + (size_t)h * G) * kD + c_q];
+    if (tid < r) c_q = channels[h * r + tid];
+    float a_q = 0.0f;
+    for (int g0 = 0; g0 < G; g0 += 8) {
+        const int ng = min(8, G - g0);
+        if (g0) __syncthreads();
+        if (tid >= 128 && tid - 128 < ng * 16) {
+            const int g = (tid - 128) >> 4, pp = (tid - 128) & 15;
+            const _Float16 *src = q + ((size_t)b * Hq + (size_t)h * G + g0 + g) * kD + pp * 8;
+            *reinterpret_cast<uint4 *>(&qrow_sh[g][pp * 8]) = *reinterpret_cast<const uint4 *>(src);
+        }
+        if (g0 == 0) {
+            if constexpr (RMODE > 0) {
+                issue(t_begin + tid);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            for (int i = tid; i < kHistBins; i += kWG) lh[i] = 0u;
+        }
+        __syncthreads();
+        if (tid < r)
+            for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
     }
-    if constexpr (RMODE > 0) {
-        issue(t_begin + tid);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    for (int i = tid; i < kHistBins; i += kWG) lh[i] = 0u;
-    if (has_q) {
-        float a = 0.0f + (float)q0;
-        for (int g = 1; g < G; ++g) a = a + (float)q[((size_t)b * Hq + (size_t)h * G + g) * kD + c_q];
-        qs_sh[j_q] = a;
-    }
+    if (tid < r) qs_sh[tid] = a_q;
     __syncthreads();
 
     DS_TR(1);
@@ -137,31 +144,51 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     DS_TR(2);
     __syncthreads();
     uint32_t *hu = hist + (size_t)u * kHistBins;
+    uint32_t *cu = coarse + (size_t)u * 256;
     {
-        uint32_t c[kHistBins / kWG];
+        // neighbouring lanes add to neighbouring words (a wavefront's atomics that fall into one
+        // cache line are served together); coarse bin tid = fine bins 16*tid .. 16*tid+15
+        uint32_t c[kHistBins / kWG], cc = 0;
 #pragma unroll
-        for (int i = 0; i < kHistBins / kWG; ++i) c[i] = lh[tid + i * kWG];
+        for (int i = 0; i < kHistBins / kWG; ++i) {
+            c[i] = lh[tid + i * kWG];
+            cc += lh[tid * 16 + i];
+        }
 #pragma unroll
         for (int i = 0; i < kHistBins / kWG; ++i)
             if (c[i]) atomicAdd(&hu[tid + i * kWG], c[i]);
+        if (cc) atomicAdd(&cu[tid], cc);
     }
 
-    // ---- last workgroup of the unit: threshold bin, then leave the histogram clean
+    // ---- last workgroup of the unit: threshold bin (coarse bin first, then its 16 fine bins),
+    // then leave the histograms clean
     DS_TR(3);
     {
         const bool last = last_arrival(&ctl[u].arrive_a, gridDim.x, &s_flag);
         DS_TR(4);
         if (!last) return;
     }
-    hist_select<kHistBins / kWG, true>([&](int bin) { return ld_dev(hu + bin); }, (uint32_t)k_eff, s_w,
-                                       s_res);
+    hist_select<1, true>([&](int bin) { return ld_dev(cu + bin); }, (uint32_t)k_eff, s_w, s_res);
+    const uint32_t cb = s_res[0], rank = s_res[1];
+    if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
+    __syncthreads();
     DS_TR(5);
     if (tid == 0) {
-        ctl[u].bstar = s_res[0];
-        ctl[u].krem = s_res[1];
+        uint32_t before = 0, bin = 0, krem = 1;
+        for (int i = 0; i < 16; ++i) {
+            if (before + s_fine[i] >= rank) {
+                bin = cb * 16 + 15 - i;
+                krem = rank - before;
+                break;
+            }
+            before += s_fine[i];
+        }
+        ctl[u].bstar = bin;
+        ctl[u].krem = krem;
         ctl[u].arrive_a = 0u;
     }
     for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
+    cu[tid] = 0u;
     DS_TR(6);
 }
 
@@ -238,8 +265,17 @@ __global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys,
     }
     const uint32_t n = ld_dev(&ctl[u].ncand);
     const bool in_lds = n <= (uint32_t)cap_lds;
-    if (in_lds)
-        for (uint32_t i = tid; i < n; i += kWG) lc[i] = ld_dev(cu + i);
+    if (in_lds) {
+        // up to four loads per thread in flight
+        for (uint32_t i0 = tid; i0 < n; i0 += kWG * 4) {
+            uint2 e[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) e[x] = ld_dev(cu + min(i0 + x * kWG, n - 1));
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (i0 + x * kWG < n) lc[i0 + x * kWG] = e[x];
+        }
+    }
     __syncthreads();
     auto at = [&](uint32_t i) { return in_lds ? lc[i] : ld_dev(cu + i); };
     DS_TR(12);
@@ -351,12 +387,13 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     const dim3 grid(p.n_sc, p.units), block(kWG);
     auto *keys = reinterpret_cast<uint32_t *>(wsp(ws, p.off_keys));
     auto *hist = reinterpret_cast<uint32_t *>(wsp(ws, p.off_hist));
+    auto *coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
     auto *ctl = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
     const auto *qh = static_cast<const _Float16 *>(q);
     const auto *lh = static_cast<const _Float16 *>(label);
     prof_begin(KID_SCORE, st);
 #define DS_SCORE(MODE)                                                                            \
-    hipLaunchKernelGGL(k_score<MODE>, grid, block, 0, st, qh, lh, channels, keys, hist, ctl, s.Hq, \
+    hipLaunchKernelGGL(k_score<MODE>, grid, block, 0, st, qh, lh, channels, keys, hist, coarse, ctl, s.Hq, \
                        s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk, p.k_eff)
     if (s.r == 8) DS_SCORE(8);
     else if (s.r == 16) DS_SCORE(16);

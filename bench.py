@@ -130,7 +130,8 @@ def main():
     if "k_fused" in kernels_us:                           # one launch does all four steps
         dom, dom_bytes = "k_fused", w.algorithmic_bytes()  # label stream + k full K and V rows (Sec. 5.3)
     else:
-        dom, dom_bytes = "k_attend", w.units * w.k * w.d * 2 * 2   # k full K and V rows per unit
+        dom = "k_refine_attend" if "k_refine_attend" in kernels_us else "k_attend"
+        dom_bytes = w.units * w.k * w.d * 2 * 2               # k full K and V rows per unit
     dom_us = kernels_us[dom]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
 

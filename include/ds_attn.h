@@ -194,7 +194,13 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
  *           workgroups when the shape and the device allow it (else three launches),
  *           3 = two launches: that co-resident launch up to the threshold candidates, then
- *           one attention launch in which every workgroup settles its unit's exact threshold
+ *           one attention launch in which every workgroup settles its unit's exact threshold,
+ *           4 = two launches: scoring (keys and threshold bin), then one launch in which a
+ *           unit's workgroups attend the rows above the threshold bin while the last of them
+ *           to have listed its candidates settles the exact threshold for the rest
+ *   knob 4: where the exact top-k threshold is settled on the three-launch path: 0 = automatic
+ *           (in the scoring launch for units of up to 8K tokens), 1 = always in a separate
+ *           candidate launch, 2 = always in the scoring launch
  * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
  * changing a knob changes ds_workspace_bytes() and the workspace layout, so
  * re-query the size and clear the workspace again afterwards.

@@ -13,8 +13,8 @@
 namespace ds {
 
 // ---------------------------------------------------------------- knobs
-static int g_tune[4] = {0, 0, 0, 0};
-int tune_get(int knob) { return (knob >= 0 && knob < 4) ? g_tune[knob] : 0; }
+static int g_tune[5] = {0, 0, 0, 0, 0};
+int tune_get(int knob) { return (knob >= 0 && knob < 5) ? g_tune[knob] : 0; }
 
 // ---------------------------------------------------------------- plans
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -97,7 +97,8 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 // ---------------------------------------------------------------- per-kernel event timing
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
-    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2"};
+    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2",
+    "k_refine_attend"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -279,8 +280,12 @@ static ds_status_t enqueue_select(const void *q, const void *label, const int32_
                                   void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
                                   hipStream_t st)
 {
-    DS_TRY(launch_score(q, label, channels, ws, p, s, st));
-    DS_TRY(launch_cand(ws, p, s, want_offsets, st));
+    // Units of up to 8K tokens: the scoring launch's last workgroup per unit also settles the
+    // exact threshold (knob 4 = 1 forces the separate candidate launch, 2 forces the tail).
+    const int mode = tune_get(4);
+    const bool tail_refine = mode == 2 || (mode == 0 && s.L <= (1 << 13));
+    DS_TRY(launch_score(q, label, channels, ws, p, s, tail_refine, want_offsets, st));
+    if (!tail_refine) DS_TRY(launch_cand(ws, p, s, want_offsets, st));
     return DS_OK;
 }
 
@@ -300,6 +305,13 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
     if (make_fused_plan(*shape, p, &f)) {
         if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
+        return DS_OK;
+    }
+    if (tune_get(3) == 4 && refine_attend_ok(p)) {
+        // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
+        // behind the attention over the rows that are selected either way
+        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st));
+        DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st));
         return DS_OK;
     }
     rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st);
@@ -423,13 +435,14 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches)
 
 ds_status_t ds_tune_set(int knob, int value)
 {
-    if (knob < 0 || knob > 3) return DS_ERR_SHAPE;
+    if (knob < 0 || knob > 4) return DS_ERR_SHAPE;
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 1 && (value % 256 != 0 || value > 4096)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 3 && value > 3) return DS_ERR_SHAPE;
+        if (knob == 3 && value > 4) return DS_ERR_SHAPE;
+        if (knob == 4 && value > 2) return DS_ERR_SHAPE;
     }
     g_tune[knob] = value;
     return DS_OK;

@@ -12,6 +12,8 @@
 // heads in a fixed order, so results are bit-reproducible whichever workgroup
 // that happens to be.
 // Logits are kept in the log2 domain: s2 = (q.k) * log2(e)/sqrt(d), p = 2^(s2-m).
+#include <algorithm>
+
 #include "ds_attend_core.h"
 
 namespace ds {
@@ -28,6 +30,11 @@ struct AttendArgs {
     float *out;
     UnitCtl *ctl_rw;
     int Hq, Hkv, G, L, L_max, key_stride, ch, n_ch, k, k_eff, n_rows;
+    // k_refine_attend only
+    uint2 *cand;         // [units][L] (key, token) of the keys in bin b*, unordered
+    uint32_t *ndef;      // [units][n_ch] keys above bin b* per chunk
+    uint32_t *offs_rw;   // [units][n_ch] offset of the chunk in the ascending index list
+    uint32_t spin_limit;
 };
 
 // MODE 0: rows = tokens of the chunk that pass the selection predicate
@@ -125,6 +132,313 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
     DS_TR(5);
 }
 
+
+// ---------------------------------------------------------------- exact threshold + attention, one launch
+// Runs after k_score has left the unit's keys and the threshold bin b* (with the
+// rank krem of the k-th key inside it).  Tokens whose key lies in a bin above b*
+// are selected whatever the exact threshold turns out to be, so a workgroup
+//   1. splits its chunk's keys into definite tokens, candidates (bin b*) and the rest,
+//      appends the candidates to the unit's list and arrives at the unit's counter;
+//   2. attends the definite rows -- the bulk of the traffic -- straight away;
+//   3. picks up the exact k-th key T and the tie cut, appends its selected
+//      candidates and attends those;
+//   4. writes its partial; the unit's last workgroup merges the partials.
+// The workgroup whose arrival completes the unit radix-selects T from the
+// candidate list before its own step 2 and publishes (T, tie cut, ready) as one
+// 64-bit word, so the refinement hides behind the other workgroups' row traffic.
+// Waiting: a workgroup waits only for the publishing workgroup, which is running
+// by then and never waits itself; every workgroup of the unit arrives before
+// any waits, and workgroups are dispatched in grid order, so all of a unit's
+// workgroups get to run as long as one XCD can hold its share of n_ch of them
+// (checked on the host).  The wait is bounded as well: on expiry the unit's error
+// word is raised and the workgroup carries on without candidates.
+template <int GT>
+__global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 1)) void k_refine_attend(AttendArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
+    uint32_t *keys_sh = dyn_sh;
+    uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
+    uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
+    __shared__ uint32_t s_w[4], s_flag, s_res[2], s_base, s_T[2], s_ok;
+    __shared__ __attribute__((aligned(16))) float red[8][kD];
+    __shared__ float red_ml[8][2];
+    __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
+    __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
+    __shared__ __attribute__((aligned(16))) float wpart[4][GT][kPartStride];
+    uint32_t *lh = reinterpret_cast<uint32_t *>(&red[0][0]);  // 1024 radix bins; red is idle until the merge
+
+    const int tid = threadIdx.x;
+    const int u = blockIdx.y, c = blockIdx.x;
+    const int b = u / a.Hkv, h = u % a.Hkv;
+    const int t0 = c * a.ch, t1 = min(a.L, t0 + a.ch);
+    const int n_pass = (t1 - t0 + kWG * 4 - 1) / (kWG * 4);  // <= 4 (ch <= 4096)
+    const uint32_t *ku = a.keys + (size_t)u * a.key_stride;
+    uint2 *cu = a.cand + (size_t)u * a.L;
+    UnitCtl *ctl = a.ctl_rw + u;
+    uint2 *ready = reinterpret_cast<uint2 *>(&ctl->cnt_a);  // {T, tie cut | 1<<31}
+    DS_TR(0);
+
+    // ---- 1. classify the chunk's keys against bin b*
+    const uint32_t bstar = ctl->bstar;
+    const uint32_t lo_key = bstar << kKeyShift;
+    uint4 kv[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int t = t0 + (p * kWG + tid) * 4;
+        kv[p] = make_uint4(0u, 0u, 0u, 0u);
+        if (p < n_pass && t < t1) kv[p] = *reinterpret_cast<const uint4 *>(ku + t);
+    }
+    int n_def = 0;
+    uint32_t n_cand = 0;
+    uint32_t cpos[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        if (p < n_pass) {
+            const int lt = (p * kWG + tid) * 4;  // offset of the thread's four tokens in the chunk
+            const uint32_t k4[4] = {kv[p].x, kv[p].y, kv[p].z, kv[p].w};
+            uint32_t packed = 0;                 // definite count | candidate count << 16
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (t0 + lt + e < t1) {
+                    keys_sh[lt + e] = k4[e];
+                    const uint32_t rel = k4[e] - lo_key;
+                    if (k4[e] >= lo_key) packed += (rel < (1u << kKeyShift)) ? 0x10000u : 1u;
+                }
+            }
+            uint32_t total;
+            const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+            int dpos = n_def + (int)(ex & 0xffffu);
+            cpos[p] = n_cand + (ex >> 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (t0 + lt + e < t1 && k4[e] >= lo_key && k4[e] - lo_key >= (1u << kKeyShift))
+                    sel[dpos++] = (uint16_t)(lt + e);
+            n_def += (int)(total & 0xffffu);
+            n_cand += total >> 16;
+        }
+    }
+    if (tid == 0) {
+        s_base = n_cand ? __hip_atomic_fetch_add(&ctl->ncand, n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        if (a.idx_out) st_dev(a.ndef + (size_t)u * a.n_ch + c, (uint32_t)n_def);
+    }
+    __syncthreads();
+    {
+        const uint32_t base = s_base;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p < n_pass) {
+                const int lt = (p * kWG + tid) * 4;
+                uint32_t k4[4] = {0u, 0u, 0u, 0u};
+                if (t0 + lt < t1) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);  // the thread's own keys
+                    k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+                }
+                uint32_t pos = base + cpos[p];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift))
+                        st_dev(cu + pos++, make_uint2(k4[e], (uint32_t)(t0 + lt + e)));
+            }
+        }
+    }
+    DS_TR(1);
+    bool have_T = last_arrival(&ctl->arrive_b, gridDim.x, &s_flag);
+    DS_TR(2);
+    uint32_t T = 0;
+    int tcut = 0x7fffffff;
+    if (have_T) {
+        // ---- the unit is complete: exact k-th key among the candidates (10 + 10 key bits), ties
+        // to the lowest token (4 + 10 + 10 index bits; tokens are below 2^24).  Up to 2048
+        // candidates stay in registers; beyond that every pass re-reads the list.
+        const uint32_t n = ld_dev(&ctl->ncand);
+        const bool in_regs = n <= 8u * kWG;
+        uint2 ce[8];
+        if (in_regs && n) {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) ce[x] = ld_dev(cu + min((uint32_t)(tid + x * kWG), n - 1));
+        }
+        auto each = [&](auto f) {
+            if (in_regs) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if ((uint32_t)(tid + x * kWG) < n) f(ce[x]);
+            } else {
+                for (uint32_t i = tid; i < n; i += kWG) f(ld_dev(cu + i));
+            }
+        };
+        DS_TR(8);
+        uint32_t krem = ctl->krem;
+        svc_radix_pass<4, true>(each, [](uint2) { return true; },
+                                [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
+        const uint32_t pre22 = (bstar << 10) | s_res[0];
+        krem = s_res[1];
+        __syncthreads();
+        svc_radix_pass<4, true>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
+                                [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
+        T = (pre22 << 10) | s_res[0];
+        const uint32_t m_ties = s_res[1];
+        const uint32_t n_ties = lh[s_res[0]];
+        __syncthreads();
+        if (m_ties < n_ties) {
+            svc_radix_pass<1, false>(each, [&](uint2 e) { return e.x == T; },
+                                     [](uint2 e) { return (e.y >> 20) & 255u; }, m_ties, lh, s_w, s_res);
+            uint32_t prefix = s_res[0], want = s_res[1];
+            __syncthreads();
+            svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+                                     [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
+            prefix = (prefix << 10) | s_res[0];
+            want = s_res[1];
+            __syncthreads();
+            svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+                                     [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
+            tcut = (int)((prefix << 10) | s_res[0]);
+            __syncthreads();
+        }
+        if (a.idx_out) {
+            // selected tokens per chunk = keys above b* + selected candidates; prefix -> offsets
+            for (int i = tid; i < a.n_ch; i += kWG) cnt[i] = ld_dev(a.ndef + (size_t)u * a.n_ch + i);
+            __syncthreads();
+            each([&](uint2 e) {
+                if (is_selected(e.x, (int)e.y, T, tcut)) atomicAdd(&cnt[e.y / (uint32_t)a.ch], 1u);
+            });
+            __syncthreads();
+            const int per = (a.n_ch + kWG - 1) / kWG;
+            const int c0 = min(a.n_ch, tid * per), c1 = min(a.n_ch, c0 + per);
+            uint32_t sum = 0;
+            for (int i = c0; i < c1; ++i) sum += cnt[i];
+            uint32_t total;
+            uint32_t run = block_exclusive_scan(sum, s_w, &total);
+            for (int i = c0; i < c1; ++i) {
+                st_dev(a.offs_rw + (size_t)u * a.n_ch + i, run);
+                run += cnt[i];
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+        if (tid == 0) {
+            st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
+            st_dev(&ctl->ncand, 0u);
+            st_dev(&ctl->arrive_b, 0u);
+        }
+        DS_TR(9);
+    }
+
+    // ---- 2..4 per pass over the query group
+    const char *Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
+    const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
+    constexpr uint32_t row_bytes = 2 * kD;
+    int n_sel = 0;
+    auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };
+    auto row_cand = [&](int ri) { return t0 + (int)sel[n_def + ri]; };
+    // After the definite rows of the first pass: fetch (T, tie cut), append the selected candidates
+    // to the row list and write the chunk's slice of the index list.
+    auto settle = [&]() {
+        if (!have_T) {
+            if (tid == 0) {
+                uint2 w = make_uint2(0u, 0u);
+                uint32_t ok = 0;
+                for (uint32_t it = 0; it < a.spin_limit; ++it) {
+                    w = ld_dev(ready);
+                    if (w.y & 0x80000000u) { ok = 1u; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                s_T[0] = w.x;
+                s_T[1] = w.y & 0x7fffffffu;
+                s_ok = ok;
+                if (!ok) st_dev(&ctl->err, 6u);
+            }
+            __syncthreads();
+            T = s_T[0];
+            tcut = (int)s_T[1];
+            if (!s_ok) { T = 0xffffffffu; tcut = -1; }  // nothing more is selected
+            have_T = true;
+        }
+        DS_TR(4);
+        const uint32_t off = a.idx_out ? ld_dev(a.offs_rw + (size_t)u * a.n_ch + c) : 0u;
+        int32_t *io = a.idx_out ? a.idx_out + (size_t)u * a.k : nullptr;
+        int all_base = 0;
+        for (int p = 0; p < n_pass; ++p) {
+            const int lt = (p * kWG + tid) * 4;
+            uint32_t k4[4] = {0u, 0u, 0u, 0u};
+            if (t0 + lt < t1) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+                k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+            }
+            bool fs[4], fc[4];
+            uint32_t packed = 0;  // selected candidates | all selected << 16
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                fs[e] = (t0 + lt + e < t1) && is_selected(k4[e], t0 + lt + e, T, tcut);
+                fc[e] = fs[e] && (k4[e] - lo_key < (1u << kKeyShift));
+                packed += (fc[e] ? 1u : 0u) + (fs[e] ? 0x10000u : 0u);
+            }
+            uint32_t total;
+            const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+            int cp = n_def + n_sel + (int)(ex & 0xffffu);
+            uint32_t ap = off + (uint32_t)all_base + (ex >> 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (fc[e]) sel[cp++] = (uint16_t)(lt + e);
+                if (io && fs[e]) {
+                    if (ap < (uint32_t)a.k_eff) io[ap] = t0 + lt + e;
+                    ++ap;
+                }
+            }
+            n_sel += (int)(total & 0xffffu);
+            all_base += (int)(total >> 16);
+        }
+        if (io && c == 0)
+            for (int i = a.k_eff + tid; i < a.k; i += kWG) io[i] = -1;
+        __syncthreads();
+    };
+
+    for (int g0 = 0; g0 < a.G; g0 += GT) {
+        float *po = a.part + (((size_t)u * a.G + g0) * a.n_ch + c) * kPartStride;
+        const _Float16 *q0 = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0) * kD;
+        __syncthreads();
+        if constexpr (GT >= 4) {
+            const int n_heads = min(GT, a.G - g0);
+            half8 qreg[4];
+            load_q_mfma(q0, n_heads, qreg);
+            MfmaState st;
+            st.init();
+            attend_rows_mfma(Ku, Vu, row_bytes, n_def, row_def, qreg, st, sc_sh[tid >> 6]);
+            if (g0 == 0) { DS_TR(3); settle(); }
+            attend_rows_mfma(Ku, Vu, row_bytes, n_sel, row_cand, qreg, st, sc_sh[tid >> 6], (n_def + 15) >> 4);
+            DS_TR(5);
+            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride);
+        } else {
+            if (tid < GT * 16) {
+                const int g = tid >> 4, p = tid & 15;
+                *reinterpret_cast<uint4 *>(&qsh[g][p * 8]) = *reinterpret_cast<const uint4 *>(q0 + (size_t)g * kD + p * 8);
+            }
+            __syncthreads();
+            RowState<GT> st;
+            st.init();
+            attend_rows<GT>(Ku, Vu, row_bytes, n_def, row_def, qsh, st);
+            if (g0 == 0) { DS_TR(3); settle(); }
+            attend_rows<GT>(Ku, Vu, row_bytes, n_sel, row_cand, qsh, st, (n_def + 15) >> 4);
+            DS_TR(5);
+            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride);
+        }
+    }
+
+    // ---- last workgroup of the unit: merge the chunk partials, leave the control words clean
+    {
+        const bool last = last_arrival(&ctl->arrive_c, gridDim.x, &s_flag);
+        DS_TR(6);
+        if (!last) return;
+    }
+    if (tid == 0) {
+        ctl->arrive_c = 0u;
+        ctl->cnt_a = 0u;
+        ctl->cnt_b = 0u;
+    }
+    merge_partials(a.part + (size_t)u * a.G * a.n_ch * kPartStride, a.G, a.n_ch,
+                   a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
+    DS_TR(7);
+}
+
 // ---------------------------------------------------------------- launchers
 static inline char *wsp(void *ws, size_t off) { return static_cast<char *>(ws) + off; }
 
@@ -171,6 +485,56 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     prof_begin(KID_ATTEND, st);
     launch_attend_mode<0>(a, dim3(p.n_ch, p.units), (size_t)p.ch * sizeof(int), st);
     prof_end(KID_ATTEND, st);
+    return hipGetLastError();
+}
+
+// Whether k_refine_attend can take this plan: chunks of at most 4096 tokens (four
+// keys per thread and pass, 16-bit row offsets), and room on one XCD for its
+// share (every eighth workgroup) of a unit's n_ch workgroups at a time.
+bool refine_attend_ok(const Plan &p)
+{
+    if (p.ch > 4096 || (p.ch & 3)) return false;
+    static int per_xcd = 0;
+    if (!per_xcd) {
+        hipDeviceProp_t prop;
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
+        per_xcd = std::max(1, prop.multiProcessorCount / 8);  // one resident workgroup per CU at least
+    }
+    return (p.n_ch + 7) / 8 <= per_xcd;
+}
+
+hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
+                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st)
+{
+    AttendArgs a{};
+    a.q = static_cast<const _Float16 *>(q);
+    a.K = static_cast<const _Float16 *>(K);
+    a.V = static_cast<const _Float16 *>(V);
+    a.keys = reinterpret_cast<const uint32_t *>(wsp(ws, p.off_keys));
+    a.ctl = reinterpret_cast<const UnitCtl *>(wsp(ws, p.off_ctl));
+    a.ctl_rw = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
+    a.out = out;
+    a.offs = reinterpret_cast<const uint32_t *>(wsp(ws, p.off_offs));
+    a.offs_rw = reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs));
+    a.cand = reinterpret_cast<uint2 *>(wsp(ws, p.off_cand));
+    a.ndef = reinterpret_cast<uint32_t *>(wsp(ws, p.off_ndef));
+    a.idx_out = idx_out;
+    a.part = reinterpret_cast<float *>(wsp(ws, p.off_part));
+    a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
+    a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
+    a.spin_limit = 1u << 21;
+    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
+    const dim3 grid(p.n_ch, p.units);
+    prof_begin(KID_REFINE_ATTEND, st);
+    switch (pick_gt(a.G)) {
+    case 16: hipLaunchKernelGGL((k_refine_attend<16>), grid, dim3(kWG), shmem, st, a); break;
+    case 8: hipLaunchKernelGGL((k_refine_attend<8>), grid, dim3(kWG), shmem, st, a); break;
+    case 4: hipLaunchKernelGGL((k_refine_attend<4>), grid, dim3(kWG), shmem, st, a); break;
+    case 2: hipLaunchKernelGGL((k_refine_attend<2>), grid, dim3(kWG), shmem, st, a); break;
+    default: hipLaunchKernelGGL((k_refine_attend<1>), grid, dim3(kWG), shmem, st, a); break;
+    }
+    prof_end(KID_REFINE_ATTEND, st);
     return hipGetLastError();
 }
 

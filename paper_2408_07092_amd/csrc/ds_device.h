@@ -203,6 +203,21 @@ __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w
     __syncthreads();
 }
 
+// One radix pass over the candidates of a unit: histogram `digit(e)` of those
+// with `match(e)`, then pick the bin holding the `want`-th of them.
+template <int PER, bool FROM_TOP, class Each, class Match, class Digit>
+__device__ __forceinline__ void svc_radix_pass(Each each, Match match, Digit digit, uint32_t want,
+                                               uint32_t *lh, uint32_t *s_w, uint32_t *res)
+{
+    for (int i = threadIdx.x; i < kWG * PER; i += kWG) lh[i] = 0u;
+    __syncthreads();
+    each([&](uint2 e) {
+        if (match(e)) atomicAdd(&lh[digit(e)], 1u);
+    });
+    __syncthreads();
+    hist_select<PER, FROM_TOP>([&](int bin) { return lh[bin]; }, want, s_w, res);
+}
+
 // Ordered compaction: writes the selected tokens of [t0, t1) to sel[] in
 // ascending token order and returns how many there are (same value in every
 // thread).  keys_u points at the unit's key array; t0 % 4 == 0.  s_w is LDS

@@ -408,21 +408,6 @@ __device__ __forceinline__ void fused_worker(const FusedArgs &a, char *smem, int
 }
 
 // ---------------------------------------------------------------- reducer
-// One radix pass over the candidates of a unit: histogram `digit(e)` of those
-// with `match(e)`, then pick the bin holding the `want`-th of them.
-template <int PER, bool FROM_TOP, class Each, class Match, class Digit>
-__device__ __forceinline__ void svc_radix_pass(Each each, Match match, Digit digit, uint32_t want,
-                                               uint32_t *lh, uint32_t *s_w, uint32_t *res)
-{
-    for (int i = threadIdx.x; i < kWG * PER; i += kWG) lh[i] = 0u;
-    __syncthreads();
-    each([&](uint2 e) {
-        if (match(e)) atomicAdd(&lh[digit(e)], 1u);
-    });
-    __syncthreads();
-    hist_select<PER, FROM_TOP>([&](int bin) { return lh[bin]; }, want, s_w, res);
-}
-
 __device__ __forceinline__ void fused_reducer(const FusedArgs &a, char *smem, int s)
 {
     __shared__ uint32_t s_w[4], s_res[2], s_ok, s_fine[16];

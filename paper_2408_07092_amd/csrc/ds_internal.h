@@ -52,6 +52,7 @@ enum KernelId {
     KID_PROBE,
     KID_FUSED,
     KID_ATTEND2,
+    KID_REFINE_ATTEND,
     KID_COUNT
 };
 
@@ -90,7 +91,8 @@ void prof_end(int id, hipStream_t st);
 // launchers: enqueue only; return the launch error (hipSuccess if fine)
 hipError_t launch_init(void *ws, size_t bytes, hipStream_t st);
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
-                        const Plan &p, const ds_shape_t &s, hipStream_t st);
+                        const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
+                        hipStream_t st);
 hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
                        hipStream_t st);
 hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,
@@ -98,6 +100,9 @@ hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_sh
 hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                                 hipStream_t st);
+bool refine_attend_ok(const Plan &p);
+hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
+                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,

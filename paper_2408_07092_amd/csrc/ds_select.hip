@@ -52,13 +52,16 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                                                const _Float16 *__restrict__ label,
                                                const int32_t *__restrict__ channels,
                                                uint32_t *__restrict__ keys, uint32_t *hist,
-                                               uint32_t *coarse, UnitCtl *ctl, int Hq, int Hkv, int G, int L, int L_max,
-                                               int r, int key_stride, int sc_chunk, int k_eff)
+                                               uint32_t *coarse, UnitCtl *ctl, uint32_t *offs, int Hq, int Hkv,
+                                               int G, int L, int L_max, int r, int key_stride, int sc_chunk,
+                                               int k_eff, int tail_refine, int want_offsets, int ch, int n_ch)
 {
+    extern __shared__ uint32_t cnt_sh[];  // n_ch words, used by the refining tail
     __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t rh[2048];
     __shared__ float qs_sh[kD];
     __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
-    __shared__ uint32_t s_w[4], s_res[2], s_flag, s_fine[16];
+    __shared__ uint32_t s_w[4], s_res[2], s_flag, s_fine[16], s_n;
     const int tid = threadIdx.x;
     const int u = blockIdx.y, b = u / Hkv, h = u % Hkv;
     const int t_begin = blockIdx.x * sc_chunk;
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                 const int t = t0 + i * kWG;
                 if (t < t_end) {
                     const uint32_t key = score_key(acc);
-                    ku[t] = key;
+                    st_dev(ku + t, key);  // written through: the unit's last workgroup may read it
                     atomicAdd(&lh[key >> kKeyShift], 1u);
                 }
             }
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     } else {
         for (int t = t_begin + tid; t < t_end; t += kWG) {
             const uint32_t key = score_key(label_dot<RMODE>(lab + (size_t)t * r, qs_sh, r));
-            ku[t] = key;
+            st_dev(ku + t, key);
             atomicAdd(&lh[key >> kKeyShift], 1u);
         }
     }
@@ -186,10 +189,134 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
         ctl[u].bstar = bin;
         ctl[u].krem = krem;
         ctl[u].arrive_a = 0u;
+        s_res[0] = bin;
+        s_res[1] = krem;
+        s_n = 0u;
     }
     for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
     cu[tid] = 0u;
+    if (!tail_refine) return;
+
+    // ---- the same workgroup settles the exact threshold: one pass over the unit's keys (all
+    // written through by now) collects the keys of bin b*, which are then radix-selected in LDS.
+    // For units of up to ~128K tokens this is cheaper than a launch that spreads the pass out.
+    __syncthreads();
+    const uint32_t bstar = s_res[0];
+    uint32_t krem = s_res[1];
+    __syncthreads();
+    uint2 *cl = reinterpret_cast<uint2 *>(lh);  // the chunk histogram is dead: 2048 candidate slots
+    constexpr uint32_t kCap = kHistBins / 2;
+    if (want_offsets)
+        for (int i = tid; i < n_ch; i += kWG) cnt_sh[i] = 0u;
+    __syncthreads();
+    // A thread's four consecutive keys lie in one attend chunk (ch % 4 == 0).  Keys of bin b*
+    // are rare, so the common case per load is a handful of compares and no branch taken.
+    const uint32_t lo_key = bstar << kKeyShift;
+    const bool ch_pow2 = (ch & (ch - 1)) == 0;
+    const int ch_shift = __builtin_ctz(ch);
+    for (int t0 = tid * 4; t0 < L; t0 += kWG * 4 * 8) {
+        uint4 kv[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int t = min(t0 + x * kWG * 4, ((L - 1) & ~3));
+            const uint2 lo = ld_dev(reinterpret_cast<const uint2 *>(ku + t));
+            const uint2 hi = ld_dev(reinterpret_cast<const uint2 *>(ku + t + 2));
+            kv[x] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+        uint32_t hits = 0;  // bit 4x+e: key e of load x lies in bin b*
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int t = t0 + x * kWG * 4;
+            const uint32_t k4[4] = {kv[x].x, kv[x].y, kv[x].z, kv[x].w};
+            uint32_t above = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t rel = k4[e] - lo_key;  // < 2^20 inside b*; wraps to huge below it
+                const bool live = t + e < L;
+                hits |= (live && rel < (1u << kKeyShift)) ? (1u << (4 * x + e)) : 0u;
+                above += (live && k4[e] >= lo_key && rel >= (1u << kKeyShift)) ? 1u : 0u;
+            }
+            if (want_offsets && above) atomicAdd(&cnt_sh[ch_pow2 ? (t >> ch_shift) : (t / ch)], above);
+        }
+        if (hits) {
+            // one returning LDS atomic per thread and batch, not one per hit
+            uint32_t slot = atomicAdd(&s_n, (uint32_t)__builtin_popcount(hits));
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                const uint32_t k4[4] = {kv[x].x, kv[x].y, kv[x].z, kv[x].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (hits & (1u << (4 * x + e))) {
+                        if (slot < kCap) cl[slot] = make_uint2(k4[e], (uint32_t)(t0 + x * kWG * 4 + e));
+                        ++slot;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
     DS_TR(6);
+    const uint32_t n = s_n;
+    const bool in_lds = n <= kCap;
+    auto each = [&](auto f) {
+        if (in_lds) {
+            for (uint32_t i = tid; i < n; i += kWG) f(cl[i]);
+        } else {
+            // more candidates than LDS slots (massive ties): walk the keys again
+            for (int t = tid; t < L; t += kWG) {
+                const uint32_t key = ld_dev(ku + t);
+                if ((key >> kKeyShift) == bstar) f(make_uint2(key, (uint32_t)t));
+            }
+        }
+    };
+    svc_radix_pass<4, true>(each, [](uint2) { return true; },
+                            [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, rh, s_w, s_res);
+    const uint32_t pre22 = (bstar << 10) | s_res[0];
+    krem = s_res[1];
+    __syncthreads();
+    svc_radix_pass<4, true>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
+                            [](uint2 e) { return e.x & 1023u; }, krem, rh, s_w, s_res);
+    const uint32_t T = (pre22 << 10) | s_res[0];
+    const uint32_t m_ties = s_res[1];
+    const uint32_t n_ties = rh[s_res[0]];
+    __syncthreads();
+    int tcut = 0x7fffffff;
+    if (m_ties < n_ties) {
+        svc_radix_pass<8, false>(each, [&](uint2 e) { return e.x == T; },
+                                 [](uint2 e) { return e.y >> 20; }, m_ties, rh, s_w, s_res);
+        uint32_t prefix = s_res[0], want = s_res[1];
+        __syncthreads();
+        svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+                                 [](uint2 e) { return (e.y >> 10) & 1023u; }, want, rh, s_w, s_res);
+        prefix = (prefix << 10) | s_res[0];
+        want = s_res[1];
+        __syncthreads();
+        svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+                                 [](uint2 e) { return e.y & 1023u; }, want, rh, s_w, s_res);
+        tcut = (int)((prefix << 10) | s_res[0]);
+        __syncthreads();
+    }
+    DS_TR(7);
+    if (tid == 0) {
+        ctl[u].T = T;
+        ctl[u].tcut = tcut;
+    }
+    if (!want_offsets) return;
+    each([&](uint2 e) {
+        if (is_selected(e.x, (int)e.y, T, tcut)) atomicAdd(&cnt_sh[e.y / (uint32_t)ch], 1u);
+    });
+    __syncthreads();
+    const int per = (n_ch + kWG - 1) / kWG;
+    const int c0 = min(n_ch, tid * per), c1 = min(n_ch, c0 + per);
+    uint32_t sum = 0;
+    for (int i = c0; i < c1; ++i) sum += cnt_sh[i];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, s_w, &total);
+    for (int i = c0; i < c1; ++i) {
+        offs[(size_t)u * n_ch + i] = run;
+        run += cnt_sh[i];
+    }
+    DS_TR(14);
 }
 
 // ---------------------------------------------------------------- candidates + exact threshold
@@ -382,19 +509,22 @@ hipError_t launch_init(void *ws, size_t bytes, hipStream_t st)
 }
 
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
-                        const Plan &p, const ds_shape_t &s, hipStream_t st)
+                        const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
+                        hipStream_t st)
 {
     const dim3 grid(p.n_sc, p.units), block(kWG);
     auto *keys = reinterpret_cast<uint32_t *>(wsp(ws, p.off_keys));
     auto *hist = reinterpret_cast<uint32_t *>(wsp(ws, p.off_hist));
     auto *coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
     auto *ctl = reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl));
+    auto *offs = reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs));
     const auto *qh = static_cast<const _Float16 *>(q);
     const auto *lh = static_cast<const _Float16 *>(label);
     prof_begin(KID_SCORE, st);
 #define DS_SCORE(MODE)                                                                            \
-    hipLaunchKernelGGL(k_score<MODE>, grid, block, 0, st, qh, lh, channels, keys, hist, coarse, ctl, s.Hq, \
-                       s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk, p.k_eff)
+    hipLaunchKernelGGL(k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, keys, hist,     \
+                       coarse, ctl, offs, s.Hq, s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk,       \
+                       p.k_eff, tail_refine ? 1 : 0, want_offsets ? 1 : 0, p.ch, p.n_ch)
     if (s.r == 8) DS_SCORE(8);
     else if (s.r == 16) DS_SCORE(16);
     else if (s.r % 8 == 0) DS_SCORE(0);

@@ -15,13 +15,20 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "three_launch"], autouse=True)
+@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend"], autouse=True)
 def decode_path(request):
-    """Every test runs on both implementations of ds_sparse_decode: the single
-    launch (workers + reducers), the two-launch and the three-launch path."""
-    ds.ds_tune_set(3, {"one_launch": 2, "two_launch": 3, "three_launch": 1}[request.param])
+    """Every test runs on every implementation of ds_sparse_decode: the single
+    launch (workers + reducers), the co-resident two-launch path, the
+    three-launch path with the exact threshold settled either in the scoring
+    launch's tail or in a candidate launch of its own, and scoring followed by
+    the launch that refines the threshold behind the attention."""
+    mode, refine = {"one_launch": (2, 0), "two_launch": (3, 0), "score_tail": (1, 2),
+                    "cand_launch": (1, 1), "refine_attend": (4, 1)}[request.param]
+    ds.ds_tune_set(3, mode)
+    ds.ds_tune_set(4, refine)
     yield request.param
     ds.ds_tune_set(3, 0)
+    ds.ds_tune_set(4, 0)
 
 
 def rand_channels(Hkv, d, r, seed, sort=True):

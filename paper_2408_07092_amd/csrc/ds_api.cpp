@@ -45,11 +45,23 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     p->sc_chunk = sc;
     p->n_sc = (s.L + sc - 1) / sc;
 
+    // Launch shape of ds_sparse_decode: single heads and pairs with long units refine the
+    // threshold behind the attention (two launches); short units refine it in the scoring tail;
+    // query groups on the matrix cores keep the candidate launch.
+    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && p->G <= 2 && s.L > (1 << 13));
     int ch = g_tune[1];
-    if (ch == 0) {
+    if (ch == 0 && p->refine_attend) {
+        // every workgroup resident at once (about six per CU) when chunks of up to 4096 allow it
+        ch = 1024;
+        while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 1536) ch *= 2;
+    } else if (ch == 0) {
         ch = (tokens >= (1 << 21)) ? 2048 : (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 512 : 256;
         if (p->G >= 4 && ch < 4096) ch *= 2;  // a query group writes G partials per chunk
         while ((s.L + ch - 1) / ch > kMaxChunks && ch < 4096) ch *= 2;
+        // The matrix-core attention holds three workgroups per CU (768 on the device).  A launch
+        // slightly over that runs a nearly empty second round: grow the chunks to fit in one.
+        if (p->G >= 4)
+            while ((int64_t)p->units * ((s.L + ch - 1) / ch) > 768 && ch < 6144 && ch < s.L) ch += 256;
     }
     p->ch = ch;
     p->n_ch = (s.L + ch - 1) / ch;
@@ -307,7 +319,7 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
     }
-    if (tune_get(3) == 4 && refine_attend_ok(p)) {
+    if (p.refine_attend && refine_attend_ok(p)) {
         // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
         // behind the attention over the rows that are selected either way
         DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st));
@@ -439,7 +451,7 @@ ds_status_t ds_tune_set(int knob, int value)
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 1 && (value % 256 != 0 || value > 4096)) return DS_ERR_SHAPE;
+        if (knob == 1 && (value % 256 != 0 || value > 6144)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 3 && value > 4) return DS_ERR_SHAPE;
         if (knob == 4 && value > 2) return DS_ERR_SHAPE;

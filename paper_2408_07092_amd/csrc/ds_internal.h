@@ -62,6 +62,7 @@ struct Plan {
     int sc_chunk, n_sc;  // tokens per workgroup / workgroups per unit, scoring
     int ch, n_ch;        // same for candidate collection, compaction and attention
     int key_stride;      // uint32 keys per unit (L rounded up to 4)
+    bool refine_attend;  // ds_sparse_decode as scoring + one refine-and-attend launch
     size_t off_ctl, off_hist, off_coarse, off_keys, off_cand, off_ndef, off_offs, off_part;
     size_t off_fused;    // data region of the single-launch path (same control prefix)
     size_t total;

@@ -45,15 +45,20 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     p->sc_chunk = sc;
     p->n_sc = (s.L + sc - 1) / sc;
 
-    // Launch shape of ds_sparse_decode: single heads and pairs with long units refine the
-    // threshold behind the attention (two launches); short units refine it in the scoring tail;
-    // query groups on the matrix cores keep the candidate launch.
-    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && p->G <= 2 && s.L > (1 << 13));
+    // Launch shape of ds_sparse_decode: units of more than 8K tokens refine the threshold behind
+    // the attention (two launches); shorter units refine it in the scoring launch's tail.
+    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && s.L > (1 << 13));
     int ch = g_tune[1];
     if (ch == 0 && p->refine_attend) {
-        // every workgroup resident at once (about six per CU) when chunks of up to 4096 allow it
-        ch = 1024;
-        while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 1536) ch *= 2;
+        // every workgroup resident at once (six per CU on the vector path, three on the matrix
+        // cores) when chunks of up to 4096 / 6144 tokens allow it
+        if (p->G <= 2) {
+            ch = 1024;
+            while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 1536) ch *= 2;
+        } else {
+            ch = 2048;
+            while (ch < 6144 && ch < s.L && (int64_t)p->units * ((s.L + ch - 1) / ch) > 768) ch += 256;
+        }
     } else if (ch == 0) {
         ch = (tokens >= (1 << 21)) ? 2048 : (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 512 : 256;
         if (p->G >= 4 && ch < 4096) ch *= 2;  // a query group writes G partials per chunk

@@ -146,32 +146,39 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // The workgroup whose arrival completes the unit radix-selects T from the
 // candidate list before its own step 2 and publishes (T, tie cut, ready) as one
 // 64-bit word, so the refinement hides behind the other workgroups' row traffic.
+// (A refiner workgroup of its own per unit was tried: it costs a place among the
+// resident workgroups and gains nothing measurable.)
 // Waiting: a workgroup waits only for the publishing workgroup, which is running
 // by then and never waits itself; every workgroup of the unit arrives before
 // any waits, and workgroups are dispatched in grid order, so all of a unit's
-// workgroups get to run as long as one XCD can hold its share of n_ch of them
-// (checked on the host).  The wait is bounded as well: on expiry the unit's error
-// word is raised and the workgroup carries on without candidates.
+// workgroups get to run as long as one XCD can hold its share (every eighth) of
+// the n_ch of them (checked on the host).  The wait is bounded as well: on expiry
+// the unit's error word is raised and the workgroup carries on without candidates.
 template <int GT>
-__global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 1)) void k_refine_attend(AttendArgs a)
+__global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(AttendArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
     uint32_t *keys_sh = dyn_sh;
     uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
     uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
     __shared__ uint32_t s_w[4], s_flag, s_res[2], s_base, s_T[2], s_ok;
-    __shared__ __attribute__((aligned(16))) float red[8][kD];
     __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
     __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
+    // 4 KiB serve the radix bins of the refinement, later the merge of the unit's partials; the
+    // workgroup's own wavefront partials lie between the two in time and share the space when
+    // they are at least that large
     __shared__ __attribute__((aligned(16))) float wpart[4][GT][kPartStride];
-    uint32_t *lh = reinterpret_cast<uint32_t *>(&red[0][0]);  // 1024 radix bins; red is idle until the merge
+    __shared__ __attribute__((aligned(16))) float red_own[GT >= 2 ? 1 : 8][kD];
+    float(*red)[kD] = GT >= 2 ? reinterpret_cast<float(*)[kD]>(&wpart[0][0][0]) : red_own;
+    uint32_t *lh = reinterpret_cast<uint32_t *>(&red[0][0]);  // 1024 radix bins
 
     const int tid = threadIdx.x;
     const int u = blockIdx.y, c = blockIdx.x;
     const int b = u / a.Hkv, h = u % a.Hkv;
     const int t0 = c * a.ch, t1 = min(a.L, t0 + a.ch);
-    const int n_pass = (t1 - t0 + kWG * 4 - 1) / (kWG * 4);  // <= 4 (ch <= 4096)
+    constexpr int kMaxPass = 6;                              // ch <= 6144
+    const int n_pass = (t1 - t0 + kWG * 4 - 1) / (kWG * 4);  // <= kMaxPass
     const uint32_t *ku = a.keys + (size_t)u * a.key_stride;
     uint2 *cu = a.cand + (size_t)u * a.L;
     UnitCtl *ctl = a.ctl_rw + u;
@@ -181,41 +188,57 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 1)) void k_refine_attend(Attend
     // ---- 1. classify the chunk's keys against bin b*
     const uint32_t bstar = ctl->bstar;
     const uint32_t lo_key = bstar << kKeyShift;
-    uint4 kv[4];
+    {
+        // all of the thread's key loads are in flight together; the keys then live in LDS
+        uint4 kv[kMaxPass];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int t = t0 + (p * kWG + tid) * 4;
-        kv[p] = make_uint4(0u, 0u, 0u, 0u);
-        if (p < n_pass && t < t1) kv[p] = *reinterpret_cast<const uint4 *>(ku + t);
+        for (int p = 0; p < kMaxPass; ++p) {
+            const int t = t0 + (p * kWG + tid) * 4;
+            kv[p] = make_uint4(0u, 0u, 0u, 0u);
+            if (p < n_pass && t < t1) kv[p] = *reinterpret_cast<const uint4 *>(ku + t);
+        }
+#pragma unroll
+        for (int p = 0; p < kMaxPass; ++p) {
+            const int lt = (p * kWG + tid) * 4;
+            if (p < n_pass && t0 + lt < t1) *reinterpret_cast<uint4 *>(keys_sh + lt) = kv[p];
+        }
     }
+    // own_keys(p): the thread's four keys of pass p (zeros past the end of the chunk)
+    auto own_keys = [&](int p, uint32_t (&k4)[4]) {
+        const int lt = (p * kWG + tid) * 4;
+        k4[0] = k4[1] = k4[2] = k4[3] = 0u;
+        if (t0 + lt < t1) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+            k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+        }
+    };
     int n_def = 0;
     uint32_t n_cand = 0;
-    uint32_t cpos[4];
+    for (int p = 0; p < n_pass; ++p) {
+        const int lt = (p * kWG + tid) * 4;  // offset of the thread's four tokens in the chunk
+        uint32_t k4[4];
+        own_keys(p, k4);
+        uint32_t packed = 0;                 // definite count | candidate count << 16
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        if (p < n_pass) {
-            const int lt = (p * kWG + tid) * 4;  // offset of the thread's four tokens in the chunk
-            const uint32_t k4[4] = {kv[p].x, kv[p].y, kv[p].z, kv[p].w};
-            uint32_t packed = 0;                 // definite count | candidate count << 16
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (t0 + lt + e < t1) {
-                    keys_sh[lt + e] = k4[e];
-                    const uint32_t rel = k4[e] - lo_key;
-                    if (k4[e] >= lo_key) packed += (rel < (1u << kKeyShift)) ? 0x10000u : 1u;
-                }
-            }
-            uint32_t total;
-            const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
-            int dpos = n_def + (int)(ex & 0xffffu);
-            cpos[p] = n_cand + (ex >> 16);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (t0 + lt + e < t1 && k4[e] >= lo_key && k4[e] - lo_key >= (1u << kKeyShift))
-                    sel[dpos++] = (uint16_t)(lt + e);
-            n_def += (int)(total & 0xffffu);
-            n_cand += total >> 16;
+        for (int e = 0; e < 4; ++e) {
+            if (t0 + lt + e < t1 && k4[e] >= lo_key)
+                packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
         }
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+        int dpos = n_def + (int)(ex & 0xffffu);
+        uint32_t cp = n_cand + (ex >> 16);
+        // candidates wait at the back of the row list, filled from its end (the front holds the
+        // definite rows; both together never exceed the chunk), until the unit-wide base is known
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (t0 + lt + e < t1 && k4[e] >= lo_key) {
+                if (k4[e] - lo_key >= (1u << kKeyShift)) sel[dpos++] = (uint16_t)(lt + e);
+                else sel[a.ch - 1 - (int)(cp++)] = (uint16_t)(lt + e);
+            }
+        }
+        n_def += (int)(total & 0xffffu);
+        n_cand += total >> 16;
     }
     if (tid == 0) {
         s_base = n_cand ? __hip_atomic_fetch_add(&ctl->ncand, n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
@@ -224,21 +247,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 1)) void k_refine_attend(Attend
     __syncthreads();
     {
         const uint32_t base = s_base;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            if (p < n_pass) {
-                const int lt = (p * kWG + tid) * 4;
-                uint32_t k4[4] = {0u, 0u, 0u, 0u};
-                if (t0 + lt < t1) {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);  // the thread's own keys
-                    k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
-                }
-                uint32_t pos = base + cpos[p];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift))
-                        st_dev(cu + pos++, make_uint2(k4[e], (uint32_t)(t0 + lt + e)));
-            }
+        for (uint32_t i = tid; i < n_cand; i += kWG) {
+            const int lt = sel[a.ch - 1 - (int)i];
+            st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
         }
     }
     DS_TR(1);
@@ -359,11 +370,8 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 1)) void k_refine_attend(Attend
         int all_base = 0;
         for (int p = 0; p < n_pass; ++p) {
             const int lt = (p * kWG + tid) * 4;
-            uint32_t k4[4] = {0u, 0u, 0u, 0u};
-            if (t0 + lt < t1) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
-                k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
-            }
+            uint32_t k4[4];
+            own_keys(p, k4);
             bool fs[4], fc[4];
             uint32_t packed = 0;  // selected candidates | all selected << 16
 #pragma unroll
@@ -488,12 +496,12 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     return hipGetLastError();
 }
 
-// Whether k_refine_attend can take this plan: chunks of at most 4096 tokens (four
-// keys per thread and pass, 16-bit row offsets), and room on one XCD for its
+// Whether k_refine_attend can take this plan: chunks of at most 6144 tokens (six
+// passes of four keys per thread, 16-bit row offsets), and room on one XCD for its
 // share (every eighth workgroup) of a unit's n_ch workgroups at a time.
 bool refine_attend_ok(const Plan &p)
 {
-    if (p.ch > 4096 || (p.ch & 3)) return false;
+    if (p.ch > 6144 || (p.ch & 3)) return false;
     static int per_xcd = 0;
     if (!per_xcd) {
         hipDeviceProp_t prop;

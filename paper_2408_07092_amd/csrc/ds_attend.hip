@@ -339,8 +339,12 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
     constexpr uint32_t row_bytes = 2 * kD;
     int n_sel = 0;
+    // First the definite rows that fill whole rounds of the four wavefronts (64 rows a round);
+    // the rest of them joins the selected candidates in one list, so that at most one round of
+    // the workgroup runs partly empty.
+    const int n_first = n_def & ~63;
     auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };
-    auto row_cand = [&](int ri) { return t0 + (int)sel[n_def + ri]; };
+    auto row_rest = [&](int ri) { return t0 + (int)sel[n_first + ri]; };
     // After the definite rows of the first pass: fetch (T, tie cut), append the selected candidates
     // to the row list and write the chunk's slice of the index list.
     auto settle = [&]() {
@@ -410,9 +414,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             load_q_mfma(q0, n_heads, qreg);
             MfmaState st;
             st.init();
-            attend_rows_mfma(Ku, Vu, row_bytes, n_def, row_def, qreg, st, sc_sh[tid >> 6]);
+            attend_rows_mfma(Ku, Vu, row_bytes, n_first, row_def, qreg, st, sc_sh[tid >> 6]);
             if (g0 == 0) { DS_TR(3); settle(); }
-            attend_rows_mfma(Ku, Vu, row_bytes, n_sel, row_cand, qreg, st, sc_sh[tid >> 6], (n_def + 15) >> 4);
+            attend_rows_mfma(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qreg, st, sc_sh[tid >> 6]);
             DS_TR(5);
             wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride);
         } else {
@@ -423,9 +427,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             __syncthreads();
             RowState<GT> st;
             st.init();
-            attend_rows<GT>(Ku, Vu, row_bytes, n_def, row_def, qsh, st);
+            attend_rows<GT>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
             if (g0 == 0) { DS_TR(3); settle(); }
-            attend_rows<GT>(Ku, Vu, row_bytes, n_sel, row_cand, qsh, st, (n_def + 15) >> 4);
+            attend_rows<GT>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
             DS_TR(5);
             wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride);
         }

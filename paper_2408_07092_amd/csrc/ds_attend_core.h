@@ -58,17 +58,14 @@ struct RowState {
     }
 };
 
-// The calling wavefront's share of the workgroup's n rows: rows w*16 + 64*i .. with
-// w = (wave - wave_shift) mod 4, so a caller with two lists in a row can hand the
-// head of the second list to the wavefronts that got the least of the first.
+// The calling wavefront's share of the workgroup's n rows: rows wave*16 + 64*i ..
 // row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
 // Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
 template <int GT, class RowOf>
 __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
-                                            RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st,
-                                            int wave_shift = 0)
+                                            RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)
 {
-    const int lane = threadIdx.x & 63, wave = ((threadIdx.x >> 6) - wave_shift) & 3;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
     for (int r0 = wave * 16; r0 < n; r0 += 64) {
         // all eight row loads of the pass are issued before the first use; lanes past the
@@ -234,9 +231,9 @@ __device__ __forceinline__ void load_q_mfma(const _Float16 *q_unit, int n_heads,
 template <class RowOf>
 __device__ __forceinline__ void attend_rows_mfma(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
                                                  RowOf row_of, const half8 (&qreg)[4], MfmaState &st,
-                                                 float *sc_lds, int wave_shift = 0)
+                                                 float *sc_lds)
 {
-    const int lane = threadIdx.x & 63, wave = ((threadIdx.x >> 6) - wave_shift) & 3;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lo = lane & 15, hi = lane >> 4;
     for (int r0 = wave * 16; r0 < n; r0 += 64) {
         // the eight 16-byte loads of the tile are issued before the first use; rows past the end

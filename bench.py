@@ -22,6 +22,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+def counted_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` as counted by rocprofv3 (FETCH_SIZE plus
+    WRITE_SIZE, each scaled by a plain kernel of known size): read from the committed counter
+    summary, None when that summary has no line for this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                tok = line.split()
+                if len(tok) >= 4 and tok[0] == "traffic_bytes_per_launch" and tok[1] == workload and tok[2] == kernel:
+                    return int(tok[3])
+    except OSError:
+        pass
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,9 +130,28 @@ def main():
             t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
+    def step_spread(fn, steps, use_graph):
+        """Per-step durations (ms) of `steps` further steps, from events between the steps."""
+        with torch.cuda.stream(stream):
+            runner = fn
+            if use_graph:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    fn()
+                runner = g.replay
+            runner()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            evs[0].record(stream)
+            for i in range(steps):
+                runner()
+                evs[i + 1].record(stream)
+            torch.cuda.synchronize()
+        return sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+
     use_graph = not args.no_graph
     ms_step, ms_step_ev = timed(sparse_sweep, args.steps, args.warmup, use_graph)
     us_layer = ms_step * 1e3 / n_layers
+    spread = step_spread(sparse_sweep, args.steps, use_graph)
 
     # ---- per-kernel durations of the same K steps (events bracketing every launch, eager)
     ds.ds_profile_reset(); ds.ds_profile_enable(True)
@@ -139,11 +174,12 @@ def main():
         "metric": "sparse decode attention us/layer at L=%d, 1/%d token sparsity (achieved HBM GB/s in extra)" % (w.L, w.L // w.k),
         "value": round(us_layer, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.note}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "L": w.L,
-                   "r": w.r, "k": w.k, "layers_per_step": n_layers, "hip_graph": use_graph},
+                   "r": w.r, "k": w.k, "storage": "f16", "layers_per_step": n_layers, "hip_graph": use_graph},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": counted_traffic(w.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
     }
     alg = w.algorithmic_bytes()
@@ -152,6 +188,7 @@ def main():
         "achieved_GBps_whole_path": round(alg / (us_layer * 1e-6) / 1e9, 1),
         "hbm_frac_whole_path": round(alg / (us_layer * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
         "us_per_layer_by_stream_events": round(ms_step_ev * 1e3 / n_layers, 3),
+        "us_per_layer_p10_p50_p90": [round(spread[int(q * (len(spread) - 1))] * 1e3 / n_layers, 3) for q in (0.1, 0.5, 0.9)],
         "attention_tokens_per_s": round(w.B / (w.n_layers * us_layer * 1e-6), 1),
         "kernels_avg_us": kernels_us,
         "setup_s": round(t_gen, 1),
@@ -245,9 +282,9 @@ def bench_offload(args, w, ds, torch, dev):
         "metric": "offload sparse decode us/layer at L=%d (K/V in pinned host memory, k=%d rows fetched per unit)" % (w.L, w.k),
         "value": round(us_layer, 2), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.note}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "L": w.L,
-                   "r": w.r, "k": w.k, "layers_per_step": n_layers},
+                   "r": w.r, "k": w.k, "storage": "f16", "layers_per_step": n_layers},
         "roofline": {"bound": "host-link", "kernel": "k_gather_host", "achieved": round(link, 1), "peak": round(h2d, 1),
                      "unit": "GB/s", "frac": round(link / h2d, 4), "traffic": None,
                      "note": "peak = measured pinned->device copy rate of this box, not a published figure"},

@@ -122,7 +122,6 @@ static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof_recs;
 static std::vector<hipEvent_t> g_prof_pool;
-static hipEvent_t g_prof_open = nullptr;
 
 static hipEvent_t prof_event()
 {
@@ -136,25 +135,18 @@ static hipEvent_t prof_event()
     return e;
 }
 
-void prof_begin(int id, hipStream_t st)
+bool prof_events(int id, hipEvent_t *start, hipEvent_t *stop)
 {
-    (void)id;
-    if (!g_prof_on) return;
+    if (!g_prof_on) return false;
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    g_prof_open = prof_event();
-    if (g_prof_open) (void)hipEventRecord(g_prof_open, st);
-}
-
-void prof_end(int id, hipStream_t st)
-{
-    if (!g_prof_on) return;
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    if (!g_prof_open) return;
-    hipEvent_t e = prof_event();
-    if (!e) { g_prof_pool.push_back(g_prof_open); g_prof_open = nullptr; return; }
-    (void)hipEventRecord(e, st);
-    g_prof_recs.push_back({id, g_prof_open, e});
-    g_prof_open = nullptr;
+    hipEvent_t a = prof_event();
+    if (!a) return false;
+    hipEvent_t b = prof_event();
+    if (!b) { g_prof_pool.push_back(a); return false; }
+    g_prof_recs.push_back({id, a, b});
+    *start = a;
+    *stop = b;
+    return true;
 }
 
 }  // namespace ds

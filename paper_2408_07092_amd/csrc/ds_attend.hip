@@ -465,14 +465,14 @@ static int pick_gt(int G)
 }
 
 template <int MODE>
-static void launch_attend_mode(const AttendArgs &a, dim3 grid, size_t shmem, hipStream_t st)
+static void launch_attend_mode(int kid, const AttendArgs &a, dim3 grid, size_t shmem, hipStream_t st)
 {
     switch (pick_gt(a.G)) {
-    case 16: hipLaunchKernelGGL((k_attend<16, MODE>), grid, dim3(kWG), shmem, st, a); break;
-    case 8: hipLaunchKernelGGL((k_attend<8, MODE>), grid, dim3(kWG), shmem, st, a); break;
-    case 4: hipLaunchKernelGGL((k_attend<4, MODE>), grid, dim3(kWG), shmem, st, a); break;
-    case 2: hipLaunchKernelGGL((k_attend<2, MODE>), grid, dim3(kWG), shmem, st, a); break;
-    default: hipLaunchKernelGGL((k_attend<1, MODE>), grid, dim3(kWG), shmem, st, a); break;
+    case 16: DS_LAUNCH(kid, (k_attend<16, MODE>), grid, dim3(kWG), shmem, st, a); break;
+    case 8: DS_LAUNCH(kid, (k_attend<8, MODE>), grid, dim3(kWG), shmem, st, a); break;
+    case 4: DS_LAUNCH(kid, (k_attend<4, MODE>), grid, dim3(kWG), shmem, st, a); break;
+    case 2: DS_LAUNCH(kid, (k_attend<2, MODE>), grid, dim3(kWG), shmem, st, a); break;
+    default: DS_LAUNCH(kid, (k_attend<1, MODE>), grid, dim3(kWG), shmem, st, a); break;
     }
 }
 
@@ -494,9 +494,7 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
     a.n_rows = 0;
-    prof_begin(KID_ATTEND, st);
-    launch_attend_mode<0>(a, dim3(p.n_ch, p.units), (size_t)p.ch * sizeof(int), st);
-    prof_end(KID_ATTEND, st);
+    launch_attend_mode<0>(KID_ATTEND, a, dim3(p.n_ch, p.units), (size_t)p.ch * sizeof(int), st);
     return hipGetLastError();
 }
 
@@ -538,15 +536,13 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.spin_limit = 1u << 21;
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
-    prof_begin(KID_REFINE_ATTEND, st);
     switch (pick_gt(a.G)) {
-    case 16: hipLaunchKernelGGL((k_refine_attend<16>), grid, dim3(kWG), shmem, st, a); break;
-    case 8: hipLaunchKernelGGL((k_refine_attend<8>), grid, dim3(kWG), shmem, st, a); break;
-    case 4: hipLaunchKernelGGL((k_refine_attend<4>), grid, dim3(kWG), shmem, st, a); break;
-    case 2: hipLaunchKernelGGL((k_refine_attend<2>), grid, dim3(kWG), shmem, st, a); break;
-    default: hipLaunchKernelGGL((k_refine_attend<1>), grid, dim3(kWG), shmem, st, a); break;
+    case 16: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<16>), grid, dim3(kWG), shmem, st, a); break;
+    case 8: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<8>), grid, dim3(kWG), shmem, st, a); break;
+    case 4: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<4>), grid, dim3(kWG), shmem, st, a); break;
+    case 2: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<2>), grid, dim3(kWG), shmem, st, a); break;
+    default: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1>), grid, dim3(kWG), shmem, st, a); break;
     }
-    prof_end(KID_REFINE_ATTEND, st);
     return hipGetLastError();
 }
 
@@ -562,9 +558,7 @@ hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void
     a.out = out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.ch = p.ch; a.n_ch = p.n_ch;
-    prof_begin(KID_DENSE, st);
-    launch_attend_mode<1>(a, dim3(p.n_ch, p.units), 0, st);
-    prof_end(KID_DENSE, st);
+    launch_attend_mode<1>(KID_DENSE, a, dim3(p.n_ch, p.units), 0, st);
     return hipGetLastError();
 }
 
@@ -580,9 +574,7 @@ hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, floa
     a.out = out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.n_rows = n_rows;
-    prof_begin(KID_ATTEND_ROWS, st);
-    launch_attend_mode<2>(a, dim3(p.n_ch, p.units), 0, st);
-    prof_end(KID_ATTEND_ROWS, st);
+    launch_attend_mode<2>(KID_ATTEND_ROWS, a, dim3(p.n_ch, p.units), 0, st);
     return hipGetLastError();
 }
 

@@ -936,16 +936,17 @@ hipError_t launch_fused(const void *q, const void *label, const void *K, const v
     a.spin_limit = 1u << 21;
     const void *fn = fused_fn(p.G, f.rmode);
     void *params[] = {&a};
-    prof_begin(KID_FUSED, st);
-    hipError_t e = hipLaunchKernel(fn, dim3(f.n_svc + f.P), dim3(kWG), params, f.lds, st);
-    prof_end(KID_FUSED, st);
+    hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    hipError_t e = prof_events(KID_FUSED, &ev_a, &ev_b)
+                       ? hipExtLaunchKernel(fn, dim3(f.n_svc + f.P), dim3(kWG), params, f.lds, st, ev_a, ev_b, 0)
+                       : hipLaunchKernel(fn, dim3(f.n_svc + f.P), dim3(kWG), params, f.lds, st);
     return e != hipSuccess ? e : hipGetLastError();
 }
 
 template <int GT>
 static void launch_attend2_gt(const Attend2Args &a, dim3 grid, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((k_attend2<GT>), grid, dim3(kWG), lds, st, a);
+    DS_LAUNCH(KID_ATTEND2, (k_attend2<GT>), grid, dim3(kWG), lds, st, a);
 }
 
 hipError_t launch_two(const void *q, const void *label, const void *K, const void *V,
@@ -982,14 +983,12 @@ hipError_t launch_two(const void *q, const void *label, const void *K, const voi
     const size_t lds = (size_t)2048 * 4 + (size_t)kCandLds * 8 + (size_t)((f.n_ch + 3) & ~3) * 8 + (size_t)m * kItemTokens * 4 + (size_t)gt * kD * 2 +
                        (size_t)4 * gt * kPartStride * 4;
     const dim3 grid(a.n_wg, p.units);
-    prof_begin(KID_ATTEND2, st);
     switch (gt) {
     case 8: launch_attend2_gt<8>(a, grid, lds, st); break;
     case 4: launch_attend2_gt<4>(a, grid, lds, st); break;
     case 2: launch_attend2_gt<2>(a, grid, lds, st); break;
     default: launch_attend2_gt<1>(a, grid, lds, st); break;
     }
-    prof_end(KID_ATTEND2, st);
     return hipGetLastError();
 }
 

@@ -86,8 +86,9 @@ bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f);
 size_t fused_workspace_bytes(const ds_shape_t &s, const Plan &p);
 
 // profiling hooks (ds_profile.cpp)
-void prof_begin(int id, hipStream_t st);
-void prof_end(int id, hipStream_t st);
+// Per-kernel timing: while it is on, prof_events hands out a start and a stop event for one
+// launch of kernel `id` (false when it is off or no event could be made) and remembers the pair.
+bool prof_events(int id, hipEvent_t *start, hipEvent_t *stop);
 
 // launchers: enqueue only; return the launch error (hipSuccess if fine)
 hipError_t launch_init(void *ws, size_t bytes, hipStream_t st);
@@ -123,3 +124,15 @@ hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream
 int tune_get(int knob);
 
 }  // namespace ds
+
+// Launches a kernel.  While per-kernel timing is on, the dispatch itself carries the start and
+// stop events, so the interval is the kernel's own begin-to-end time without the launch latency
+// that events recorded around the launch would add.
+#define DS_LAUNCH(kid, kernel, grid, block, shmem, st, ...)                                          \
+    do {                                                                                             \
+        hipEvent_t ds_ev_a_ = nullptr, ds_ev_b_ = nullptr;                                           \
+        if (ds::prof_events((kid), &ds_ev_a_, &ds_ev_b_))                                            \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, st, ds_ev_a_, ds_ev_b_, 0, __VA_ARGS__); \
+        else                                                                                         \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                         \
+    } while (0)

@@ -75,22 +75,18 @@ hipError_t launch_label(const void *K, const int32_t *channels, void *label, con
     const size_t total = (size_t)n * s.r;
     size_t blocks = (total + kWG - 1) / kWG;
     if (blocks > 4096) blocks = 4096;
-    prof_begin(KID_LABEL, st);
-    hipLaunchKernelGGL(k_label, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
+    DS_LAUNCH(KID_LABEL, k_label, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
                        static_cast<const uint16_t *>(K), channels, static_cast<uint16_t *>(label),
                        s.Hkv, s.L_max, s.r, t0, n);
-    prof_end(KID_LABEL, st);
     return hipGetLastError();
 }
 
 hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,
                               const ds_shape_t &s, hipStream_t st)
 {
-    prof_begin(KID_GATHER_HOST, st);
-    hipLaunchKernelGGL(k_gather_host, dim3((s.k + 15) / 16, s.B * s.Hkv), dim3(kWG), 0, st,
+    DS_LAUNCH(KID_GATHER_HOST, k_gather_host, dim3((s.k + 15) / 16, s.B * s.Hkv), dim3(kWG), 0, st,
                        static_cast<const uint4 *>(Kh), static_cast<const uint4 *>(Vh), idx,
                        static_cast<uint4 *>(rows), s.L_max, s.k);
-    prof_end(KID_GATHER_HOST, st);
     return hipGetLastError();
 }
 
@@ -98,10 +94,8 @@ hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream
 {
     const size_t n16 = bytes / 16;
     const size_t blocks = (n16 + kWG * 8 - 1) / (kWG * 8);
-    prof_begin(KID_PROBE, st);
-    hipLaunchKernelGGL(k_probe, dim3((unsigned)blocks), dim3(kWG), 0, st,
+    DS_LAUNCH(KID_PROBE, k_probe, dim3((unsigned)blocks), dim3(kWG), 0, st,
                        static_cast<const uint4 *>(src), n16, sink);
-    prof_end(KID_PROBE, st);
     return hipGetLastError();
 }
 

@@ -502,9 +502,7 @@ hipError_t launch_init(void *ws, size_t bytes, hipStream_t st)
     size_t blocks = (n16 + kWG * 4 - 1) / (kWG * 4);
     if (blocks < 1) blocks = 1;
     if (blocks > 65536) blocks = 65536;
-    prof_begin(KID_INIT, st);
-    hipLaunchKernelGGL(k_init, dim3((unsigned)blocks), dim3(kWG), 0, st, static_cast<uint4 *>(ws), n16);
-    prof_end(KID_INIT, st);
+    DS_LAUNCH(KID_INIT, k_init, dim3((unsigned)blocks), dim3(kWG), 0, st, static_cast<uint4 *>(ws), n16);
     return hipGetLastError();
 }
 
@@ -520,9 +518,8 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     auto *offs = reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs));
     const auto *qh = static_cast<const _Float16 *>(q);
     const auto *lh = static_cast<const _Float16 *>(label);
-    prof_begin(KID_SCORE, st);
 #define DS_SCORE(MODE)                                                                            \
-    hipLaunchKernelGGL(k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, keys, hist,     \
+    DS_LAUNCH(KID_SCORE, k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, keys, hist,     \
                        coarse, ctl, offs, s.Hq, s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk,       \
                        p.k_eff, tail_refine ? 1 : 0, want_offsets ? 1 : 0, p.ch, p.n_ch)
     if (s.r == 8) DS_SCORE(8);
@@ -530,7 +527,6 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     else if (s.r % 8 == 0) DS_SCORE(0);
     else DS_SCORE(-1);
 #undef DS_SCORE
-    prof_end(KID_SCORE, st);
     return hipGetLastError();
 }
 
@@ -539,28 +535,24 @@ hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_o
 {
     const int cap_lds = p.ch > 2048 ? p.ch : 2048;
     const size_t shmem = (size_t)cap_lds * sizeof(uint2) + (size_t)p.n_ch * sizeof(uint32_t);
-    prof_begin(KID_CAND, st);
-    hipLaunchKernelGGL(k_cand, dim3(p.n_ch, p.units), dim3(kWG), shmem, st,
+    DS_LAUNCH(KID_CAND, k_cand, dim3(p.n_ch, p.units), dim3(kWG), shmem, st,
                        reinterpret_cast<const uint32_t *>(wsp(ws, p.off_keys)),
                        reinterpret_cast<UnitCtl *>(wsp(ws, p.off_ctl)),
                        reinterpret_cast<uint2 *>(wsp(ws, p.off_cand)),
                        reinterpret_cast<uint32_t *>(wsp(ws, p.off_ndef)),
                        reinterpret_cast<uint32_t *>(wsp(ws, p.off_offs)), s.L, p.key_stride, p.ch,
                        p.n_ch, cap_lds, want_offsets ? 1 : 0);
-    prof_end(KID_CAND, st);
     return hipGetLastError();
 }
 
 hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                           hipStream_t st)
 {
-    prof_begin(KID_COMPACT, st);
-    hipLaunchKernelGGL(k_compact, dim3(p.n_ch, p.units), dim3(kWG), (size_t)p.ch * sizeof(int), st,
+    DS_LAUNCH(KID_COMPACT, k_compact, dim3(p.n_ch, p.units), dim3(kWG), (size_t)p.ch * sizeof(int), st,
                        reinterpret_cast<const uint32_t *>(wsp(ws, p.off_keys)),
                        reinterpret_cast<const UnitCtl *>(wsp(ws, p.off_ctl)),
                        reinterpret_cast<const uint32_t *>(wsp(ws, p.off_offs)), idx_out, s.L,
                        p.key_stride, p.ch, p.n_ch, s.k, p.k_eff);
-    prof_end(KID_COMPACT, st);
     return hipGetLastError();
 }
 

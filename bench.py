@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--tune", default="", help="knob=value,... (ds_tune_set)")
+    ap.add_argument("--label-ablation", action="store_true",
+                    help="with / without label cache over the batch x length grid of the paper's ablation table")
     return ap.parse_args()
 
 
@@ -73,6 +75,8 @@ def main():
         kn, val = kv.split("=")
         ds.ds_tune_set(int(kn), int(val))
 
+    if args.label_ablation:
+        return bench_label_ablation(args, ds, torch, dev)
     if w.name == "C5":
         return bench_offload(args, w, ds, torch, dev)
 
@@ -96,10 +100,15 @@ def main():
     t_gen = time.time() - t_gen
     ws = ds.ds_workspace_alloc(shp, dev)
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()   # set-up ran on the default stream, the timed work does not
 
     def sparse_sweep():
         for (q, label, K, V, ch) in layers:
             ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+
+    def nolabel_sweep():
+        for (q, label, K, V, ch) in layers:
+            ds.ds_sparse_decode_nolabel(q, K, V, ch, out, None, ws, shp)
 
     def dense_sweep():
         for (q, label, K, V, ch) in layers:
@@ -203,6 +212,12 @@ def main():
         extra["dense_achieved_GBps"] = round(w.dense_bytes() / (d_us * 1e-6) / 1e9, 1)
         extra["speedup_vs_dense"] = round(d_us / us_layer, 3)
 
+    # ---- the same decode scoring straight from the K rows (what the label cache buys; Sec. 4.2)
+    if not args.no_dense:
+        n_ms, _ = timed(nolabel_sweep, max(2, args.steps // 4), 1, use_graph)
+        extra["nolabel_us_per_layer"] = round(n_ms * 1e3 / n_layers, 3)
+        extra["label_cache_speedup"] = round(n_ms * 1e3 / n_layers / us_layer, 3)
+
     # ---- measured read ceiling of this device: plain 16-byte loads over one layer's K cache at a time
     sink = torch.zeros(1024, dtype=torch.int32, device=dev)
 
@@ -236,6 +251,67 @@ def main():
     print(json.dumps(res))
 
 
+def bench_label_ablation(args, ds, torch, dev):
+    """The grid of the appendix table "Latency with and without label cache": batch 4 and 32,
+    2K to 16K tokens, Llama-2-7B attention shape (32 heads, d = 128), 1/16 channel and token
+    sparsity.  One attention layer per call; distinct layer caches are rotated so that no call
+    finds its data in a cache.  The paper's milliseconds are another machine's: only the shape of
+    the table (label cache faster by a factor) is comparable."""
+    from workloads import Workload, make_calibration_numpy, make_layer_torch
+    rows = []
+    stream = torch.cuda.Stream(device=dev)
+    for B in (4, 32):
+        for L in (2048, 4096, 8192, 16384):
+            w = Workload(f"abl_B{B}_L{L}", B, 32, 32, 128, L, 8, L // 16, 32)
+            layer_bytes = w.units * L * (2 * w.d * 2 + w.r * 2)
+            n_layers = max(2, min(16, (4 << 30) // layer_bytes))
+            shp = ds.shape(w.B, w.Hq, w.Hkv, w.d, L, L, w.r, w.k)
+            layers = []
+            for l in range(n_layers):
+                qc, kc = make_calibration_numpy(w, layer=l)
+                ch = torch.from_numpy(ds.ds_calibrate_channels(qc, kc, w.r, ds.DS_CALIB_QK)).to(dev)
+                t = make_layer_torch(w, dev, layer=l)
+                label = torch.empty((w.B, w.Hkv, L, w.r), dtype=torch.float16, device=dev)
+                ds.ds_build_label(t["K"], ch, label, shp)
+                layers.append((t["q"], label, t["K"], t["V"], ch))
+            ws = ds.ds_workspace_alloc(shp, dev)
+            out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+            torch.cuda.synchronize()   # set-up ran on the default stream, the timed work does not
+
+            def with_label():
+                for (q, label, K, V, ch) in layers:
+                    ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+
+            def without_label():
+                for (q, label, K, V, ch) in layers:
+                    ds.ds_sparse_decode_nolabel(q, K, V, ch, out, None, ws, shp)
+
+            us = []
+            for fn in (with_label, without_label):
+                with torch.cuda.stream(stream):
+                    fn(); stream.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=stream):
+                        fn()
+                    for _ in range(args.warmup):
+                        g.replay()
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(args.steps):
+                        g.replay()
+                    torch.cuda.synchronize()
+                    us.append((time.perf_counter() - t0) * 1e6 / args.steps / n_layers)
+            rows.append({"B": B, "L": L, "with_label_us": round(us[0], 2), "without_label_us": round(us[1], 2),
+                         "speedup": round(us[1] / us[0], 2), "layer_caches": n_layers})
+            del layers, ws, out
+            torch.cuda.empty_cache()
+    print(json.dumps({"metric": "sparse decode attention us/layer with and without label cache",
+                      "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": "label-cache ablation grid: H32/32 d128 r8 k=L/16", "storage": "f16"},
+                      "rows": rows}))
+
+
 def bench_offload(args, w, ds, torch, dev):
     """Config 5: K/V in pinned host memory, label cache on the GPU; per layer select on the GPU,
     fetch the k rows over the host link (double-buffered across layers), attend over them."""
@@ -258,6 +334,7 @@ def bench_offload(args, w, ds, torch, dev):
         layers.append((t["q"], label, ch, t["K"], t["V"]))
         outs.append(torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev))
     dec = OffloadDecoder(shp, dev)
+    torch.cuda.synchronize()
     for _ in range(args.warmup):
         dec.decode(layers, outs)
     torch.cuda.synchronize()

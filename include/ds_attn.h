@@ -115,7 +115,10 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
  * (a multiple of 256).  Pure host function; 0 if the shape is invalid. */
 size_t ds_workspace_bytes(const ds_shape_t *shape);
 /* Enqueues the clearing of a freshly allocated workspace (all workspace_bytes,
- * a multiple of 16).  Required once before the first call that uses it. */
+ * a multiple of 16).  Required once before the first call that uses it: the
+ * clearing must have completed, or be ordered on the same stream, before that
+ * call runs.  A call on a workspace that was not cleared gives wrong results
+ * (out-of-range counters are caught where they would index memory). */
 ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -134,6 +137,20 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K,
                              int32_t *idx_out, void *workspace,
                              size_t workspace_bytes, const ds_shape_t *shape,
                              void *stream);
+
+/*
+ * The same decode without a label cache (Sec. 4.2 and the appendix ablation
+ * "Forward without Label Cache"): s_hat[t] is formed from K[t, channels[j]] read
+ * out of the 256-byte K rows, the strided access the label cache removes.  Same
+ * arithmetic as ds_sparse_decode, hence the same selection and output for a
+ * label cache that matches K; it exists to measure what the label cache buys.
+ * Arguments as ds_sparse_decode, minus label.
+ */
+ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V,
+                                     const int32_t *channels, float *out,
+                                     int32_t *idx_out, void *workspace,
+                                     size_t workspace_bytes, const ds_shape_t *shape,
+                                     void *stream);
 
 /*
  * Dense decode attention over all L tokens (Sec. 2.1), the in-library

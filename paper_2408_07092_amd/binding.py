@@ -22,7 +22,8 @@ DS_CALIB_Q, DS_CALIB_K, DS_CALIB_QK = 0, 1, 2
 
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
-    "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_dense_decode", "ds_select",
+    "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_sparse_decode_nolabel",
+    "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
     "ds_tune_set", "ds_tune_get",
@@ -63,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.ds_workspace_bytes.argtypes = [shp]
         L.ds_workspace_init.argtypes = [vp, sz, vp]
         L.ds_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
+        L.ds_sparse_decode_nolabel.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_dense_decode.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_select.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_gather_rows_host.argtypes = [vp, vp, vp, vp, shp, vp]
@@ -146,12 +148,14 @@ def ds_workspace_init(workspace, stream=None):
 
 
 def ds_workspace_alloc(shp: DsShape, device="cuda") -> "torch.Tensor":
-    """torch-allocated, cleared workspace for `shp` (convenience of the binding)."""
+    """torch-allocated, cleared workspace for `shp` (convenience of the binding).  The clearing
+    runs on the current stream and is waited for, so the workspace may be used on any stream."""
     n = ds_workspace_bytes(shp)
     if n == 0:
         raise DsError(DS_ERR_SHAPE, "ds_workspace_bytes")
     ws = torch.empty(n, dtype=torch.uint8, device=device)
     ds_workspace_init(ws)
+    torch.cuda.current_stream(ws.device).synchronize()
     return ws
 
 
@@ -160,6 +164,13 @@ def ds_sparse_decode(q, label, K, V, channels, out, idx_out, workspace, shp: DsS
                                   _dp(idx_out), _dp(workspace),
                                   workspace.numel() * workspace.element_size(),
                                   ctypes.byref(shp), _stream(stream)), "ds_sparse_decode")
+
+
+def ds_sparse_decode_nolabel(q, K, V, channels, out, idx_out, workspace, shp: DsShape, stream=None):
+    _check(lib().ds_sparse_decode_nolabel(_dp(q), _dp(K), _dp(V), _dp(channels), _dp(out),
+                                          _dp(idx_out), _dp(workspace),
+                                          workspace.numel() * workspace.element_size(),
+                                          ctypes.byref(shp), _stream(stream)), "ds_sparse_decode_nolabel")
 
 
 def ds_dense_decode(q, K, V, out, workspace, shp: DsShape, stream=None):

@@ -287,21 +287,23 @@ static ds_status_t select_common(const void *q, const void *label, const int32_t
 
 static ds_status_t enqueue_select(const void *q, const void *label, const int32_t *channels,
                                   void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
-                                  hipStream_t st)
+                                  hipStream_t st, bool label_is_k = false)
 {
     // Units of up to 8K tokens: the scoring launch's last workgroup per unit also settles the
     // exact threshold (knob 4 = 1 forces the separate candidate launch, 2 forces the tail).
     const int mode = tune_get(4);
     const bool tail_refine = mode == 2 || (mode == 0 && s.L <= (1 << 13));
-    DS_TRY(launch_score(q, label, channels, ws, p, s, tail_refine, want_offsets, st));
+    DS_TRY(launch_score(q, label, channels, ws, p, s, tail_refine, want_offsets, st, label_is_k));
     if (!tail_refine) DS_TRY(launch_cand(ws, p, s, want_offsets, st));
     return DS_OK;
 }
 
-ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, const void *V,
-                             const int32_t *channels, float *out, int32_t *idx_out,
-                             void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
-                             void *stream)
+// ds_sparse_decode with the scores taken either from the label cache or (label_is_k) from the K
+// rows themselves.
+static ds_status_t sparse_decode_impl(const void *q, const void *label, const void *K, const void *V,
+                                      const int32_t *channels, float *out, int32_t *idx_out,
+                                      void *workspace, size_t workspace_bytes,
+                                      const ds_shape_t *shape, void *stream, bool label_is_k)
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
@@ -311,7 +313,7 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     FusedPlan f;
-    if (make_fused_plan(*shape, p, &f)) {
+    if (!label_is_k && make_fused_plan(*shape, p, &f)) {
         if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
@@ -319,14 +321,32 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
     if (p.refine_attend && refine_attend_ok(p)) {
         // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
         // behind the attention over the rows that are selected either way
-        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st));
+        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, label_is_k));
         DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st));
         return DS_OK;
     }
-    rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st);
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st, label_is_k);
     if (rc != DS_OK) return rc;
     DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st));
     return DS_OK;
+}
+
+ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, const void *V,
+                             const int32_t *channels, float *out, int32_t *idx_out,
+                             void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                             void *stream)
+{
+    return sparse_decode_impl(q, label, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
+                              stream, false);
+}
+
+ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V,
+                                     const int32_t *channels, float *out, int32_t *idx_out,
+                                     void *workspace, size_t workspace_bytes,
+                                     const ds_shape_t *shape, void *stream)
+{
+    return sparse_decode_impl(q, K, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
+                              stream, true);
 }
 
 ds_status_t ds_select(const void *q, const void *label, const int32_t *channels, int32_t *idx_out,

@@ -246,10 +246,15 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     }
     __syncthreads();
     {
+        // (a unit has L candidates at most; a base beyond that means the workspace was not cleared)
         const uint32_t base = s_base;
-        for (uint32_t i = tid; i < n_cand; i += kWG) {
-            const int lt = sel[a.ch - 1 - (int)i];
-            st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
+        if (base + n_cand <= (uint32_t)a.L) {
+            for (uint32_t i = tid; i < n_cand; i += kWG) {
+                const int lt = sel[a.ch - 1 - (int)i];
+                st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
+            }
+        } else if (tid == 0) {
+            st_dev(&ctl->err, 8u);
         }
     }
     DS_TR(1);
@@ -261,7 +266,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
         // ---- the unit is complete: exact k-th key among the candidates (10 + 10 key bits), ties
         // to the lowest token (4 + 10 + 10 index bits; tokens are below 2^24).  Up to 2048
         // candidates stay in registers; beyond that every pass re-reads the list.
-        const uint32_t n = ld_dev(&ctl->ncand);
+        const uint32_t n = min(ld_dev(&ctl->ncand), (uint32_t)a.L);
         const bool in_regs = n <= 8u * kWG;
         uint2 ce[8];
         if (in_regs && n) {

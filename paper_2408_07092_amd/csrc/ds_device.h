@@ -169,12 +169,18 @@ __device__ __forceinline__ float block_sum(float x, float *s_w)
 // bin holding the kth element (1-based) counted from the top bin down
 // (FROM_TOP) or from bin 0 up.  res[0] = bin, res[1] = rank of the element
 // inside that bin, counted the same way.  Exactly one thread writes res when
-// 1 <= kth <= total count; all threads may read res after the call.
+// 1 <= kth <= total count (otherwise res = {0, 1}); all threads may read res
+// after the call, and must have finished reading an earlier result before it.
 template <int PER, bool FROM_TOP, class Get>
 __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w, uint32_t *res)
 {
     const int tid = threadIdx.x;
     constexpr int NB = kWG * PER;
+    // in-range result even when the counts do not reach kth (a workspace that was not cleared)
+    if (tid == 0) {
+        res[0] = 0u;
+        res[1] = 1u;
+    }
     uint32_t loc[PER];
     uint32_t sum = 0;
 #pragma unroll

@@ -94,7 +94,7 @@ bool prof_events(int id, hipEvent_t *start, hipEvent_t *stop);
 hipError_t launch_init(void *ws, size_t bytes, hipStream_t st);
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
                         const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
-                        hipStream_t st);
+                        hipStream_t st, bool label_is_k = false);
 hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
                        hipStream_t st);
 hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,

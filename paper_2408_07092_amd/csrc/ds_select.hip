@@ -30,7 +30,10 @@ __global__ __launch_bounds__(kWG) void k_init(uint4 *p, size_t n16)
 
 // ---------------------------------------------------------------- score
 // RMODE 8 / 16: r known at compile time (one or two 16-byte loads per token);
-// RMODE 0: r % 8 == 0 (r/8 16-byte loads); RMODE -1: any r, 2-byte loads.
+// RMODE 0: r % 8 == 0 (r/8 16-byte loads); RMODE -1: any r, 2-byte loads;
+// RMODE -2: no label cache -- `label` is the K cache itself and the r channels of a token are
+// picked out of its 256-byte row, the access pattern the label cache exists to avoid (Sec. 4.2,
+// ablation in the appendix "Forward without Label Cache").  Same arithmetic, same keys.
 template <int RMODE>
 __device__ __forceinline__ float label_dot(const _Float16 *__restrict__ row, const float *qs, int r)
 {
@@ -60,6 +63,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     __shared__ uint32_t lh[kHistBins];
     __shared__ uint32_t rh[2048];
     __shared__ float qs_sh[kD];
+    __shared__ int ch_sh[kD];
     __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
     __shared__ uint32_t s_w[4], s_res[2], s_flag, s_fine[16], s_n;
     const int tid = threadIdx.x;
@@ -111,7 +115,10 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
         if (tid < r)
             for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
     }
-    if (tid < r) qs_sh[tid] = a_q;
+    if (tid < r) {
+        qs_sh[tid] = a_q;
+        ch_sh[tid] = c_q;
+    }
     __syncthreads();
 
     DS_TR(1);
@@ -136,6 +143,30 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
             }
             t0 += kWG * UNR;
             if (t0 < t_end) issue(t0);
+        }
+    } else if constexpr (RMODE == -2) {
+        const _Float16 *Ku = label + (size_t)u * L_max * kD;
+        for (int t0 = t_begin + tid; t0 < t_end; t0 += kWG * 4) {
+            const _Float16 *row[4];
+            float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) row[i] = Ku + (size_t)min(t0 + i * kWG, t_end - 1) * kD;
+#pragma unroll 8
+            for (int j = 0; j < r; ++j) {
+                const int cj = ch_sh[j];
+                const float qj = qs_sh[j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] = __builtin_fmaf(qj, (float)row[i][cj], acc[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = t0 + i * kWG;
+                if (t < t_end) {
+                    const uint32_t key = score_key(acc[i]);
+                    st_dev(ku + t, key);
+                    atomicAdd(&lh[key >> kKeyShift], 1u);
+                }
+            }
         }
     } else {
         for (int t = t_begin + tid; t < t_end; t += kWG) {
@@ -379,8 +410,13 @@ __global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys,
     }
     __syncthreads();
     {
+        // (a unit has L candidates at most; a base beyond that means the workspace was not cleared)
         const uint32_t n = s_cnt, base = s_base;
-        for (uint32_t i = tid; i < n; i += kWG) st_dev(cu + base + i, lc[i]);
+        if (base + n <= (uint32_t)L) {
+            for (uint32_t i = tid; i < n; i += kWG) st_dev(cu + base + i, lc[i]);
+        } else if (tid == 0) {
+            st_dev(&ctl[u].err, 8u);
+        }
     }
 
     // ---- last workgroup of the unit: exact k-th key among the candidates
@@ -390,7 +426,7 @@ __global__ __launch_bounds__(kWG) void k_cand(const uint32_t *__restrict__ keys,
         DS_TR(11);
         if (!last) return;
     }
-    const uint32_t n = ld_dev(&ctl[u].ncand);
+    const uint32_t n = min(ld_dev(&ctl[u].ncand), (uint32_t)L);
     const bool in_lds = n <= (uint32_t)cap_lds;
     if (in_lds) {
         // up to four loads per thread in flight
@@ -508,7 +544,7 @@ hipError_t launch_init(void *ws, size_t bytes, hipStream_t st)
 
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
                         const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
-                        hipStream_t st)
+                        hipStream_t st, bool label_is_k)
 {
     const dim3 grid(p.n_sc, p.units), block(kWG);
     auto *keys = reinterpret_cast<uint32_t *>(wsp(ws, p.off_keys));
@@ -522,7 +558,8 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     DS_LAUNCH(KID_SCORE, k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, keys, hist,     \
                        coarse, ctl, offs, s.Hq, s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk,       \
                        p.k_eff, tail_refine ? 1 : 0, want_offsets ? 1 : 0, p.ch, p.n_ch)
-    if (s.r == 8) DS_SCORE(8);
+    if (label_is_k) DS_SCORE(-2);
+    else if (s.r == 8) DS_SCORE(8);
     else if (s.r == 16) DS_SCORE(16);
     else if (s.r % 8 == 0) DS_SCORE(0);
     else DS_SCORE(-1);

@@ -75,6 +75,13 @@ class Case:
         torch.cuda.synchronize()
         return out.cpu().numpy(), (idx.cpu().numpy() if want_idx else None)
 
+    def gpu_sparse_nolabel(self):
+        out = torch.full((self.B, self.Hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
+        idx = torch.full((self.B, self.Hkv, self.k), -7, dtype=torch.int32, device="cuda")
+        ds.ds_sparse_decode_nolabel(self.q, self.K, self.V, self.ch, out, idx, self.ws, self.shape)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), idx.cpu().numpy()
+
     def gpu_dense(self):
         out = torch.full((self.B, self.Hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
         ds.ds_dense_decode(self.q, self.K, self.V, out, self.ws, self.shape)
@@ -170,6 +177,12 @@ def full_parity(case: Case, check_dense=True, what=""):
     assert out_gpu2.tobytes() == out_gpu.tobytes(), f"{what}: output depends on idx_out / not reproducible"
     # ds_select alone gives the same list
     assert np.array_equal(case.gpu_select(), idx_gpu), f"{what}: ds_select differs from ds_sparse_decode"
+    # scoring straight from the K rows (no label cache): same selection as the binary32-order
+    # oracle, output to the same bar
+    out_nl, idx_nl = case.gpu_sparse_nolabel()
+    check_index_structure(idx_nl, case.L, case.k)
+    assert np.array_equal(idx_nl, idx32), f"{what}: no-label index sets differ from the binary32-order oracle"
+    check_output(out_nl, ref, what + " sparse, no label cache")
     rep = {"abs_err": abs_err, "rel_err": rel_err, "units_differing_in_band": differing}
     if check_dense:
         d_gpu = case.gpu_dense()

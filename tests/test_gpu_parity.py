@@ -310,6 +310,28 @@ def test_full_config_c5_offload_rows_from_pinned_host():
     print("C5", check_output(out.cpu().numpy(), ref_out, "C5 offload"))
 
 
+def test_nolabel_rejects_bad_arguments_and_matches_label_path_bytes():
+    w = WORKLOADS["C1"]
+    t = make_layer_numpy(w)
+    case = Case(t["q"], t["K"], t["V"], outlier_channels(w.Hkv, w.d), w.L, w.k)
+    case.gpu_build_label()
+    out_l, idx_l = case.gpu_sparse()
+    out_n, idx_n = case.gpu_sparse_nolabel()
+    assert np.array_equal(idx_l, idx_n)
+    if ds.ds_tune_get(3) not in (2, 3):        # the co-resident launches order their partial sums differently
+        assert out_l.tobytes() == out_n.tobytes()
+    out = torch.zeros((case.B, case.Hq, case.d), dtype=torch.float32, device="cuda")
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_sparse_decode_nolabel(case.q, None, case.V, case.ch, out, None, case.ws, case.shape)
+    assert e.value.status == ds.DS_ERR_NULL
+    bad = ds.shape(case.B, case.Hq, case.Hkv, case.d, case.L_max + 1, case.L_max, case.r, case.k)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_sparse_decode_nolabel(case.q, case.K, case.V, case.ch, out, None, case.ws, bad)
+    assert e.value.status == ds.DS_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert float(out.abs().max()) == 0.0
+
+
 # ---------------------------------------------------------------- determinism across tuning-independent reruns
 def test_run_to_run_bytes_identical_c1_many_times():
     w = WORKLOADS["C1"]

@@ -111,6 +111,34 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
                             const ds_shape_t *shape, int32_t t0, int32_t n_new,
                             void *stream);
 
+/*
+ * K/V cache layouts.  DS_KV_SPLIT: K and V are separate [B, Hkv, L_max, d]
+ * arrays (the layout of every call above and below unless it says otherwise).
+ * DS_KV_INTERLEAVED: one array KV [B, Hkv, L_max, 2, d] in which a token's K
+ * row is followed by its V row, so that the decode gathers one 512-byte piece
+ * per selected token instead of two 256-byte rows (Sec. 5.3: the cost of the
+ * path is the gather of the selected rows).  KV base 256-byte aligned;
+ * L_max * 512 must fit 32 bits.
+ */
+typedef enum { DS_KV_SPLIT = 0, DS_KV_INTERLEAVED = 1 } ds_kv_layout_t;
+
+/*
+ * Decode-step cache maintenance in one launch (Sec. 4.2: in the decoding phase
+ * only the heavy-channel values of the new tokens are added to the label
+ * cache).  Writes the n_new new tokens' rows k_new, v_new [B, Hkv, n_new, d]
+ * fp16 (device, 16-byte aligned) into the caches at tokens [t0, t0 + n_new) and
+ * label[b, h, t0 + i, j] = k_new[b, h, i, channels[h, j]].  With
+ * DS_KV_INTERLEAVED pass the KV array as K; V is ignored.  Uses
+ * shape->{B, Hkv, d, L_max, r}; t0 + n_new <= L_max.  Equal to copying the rows
+ * and calling ds_append_label.
+ */
+ds_status_t ds_append_kv(const void *k_new, const void *v_new, void *K, void *V,
+                         const int32_t *channels, void *label, const ds_shape_t *shape,
+                         int32_t t0, int32_t n_new, ds_kv_layout_t layout, void *stream);
+/* ds_build_label for an interleaved cache KV [B, Hkv, L_max, 2, d]. */
+ds_status_t ds_build_label_kv(const void *KV, const int32_t *channels, void *label,
+                              const ds_shape_t *shape, void *stream);
+
 /* Bytes of workspace any decode/select/attend call with this shape needs
  * (a multiple of 256).  Pure host function; 0 if the shape is invalid. */
 size_t ds_workspace_bytes(const ds_shape_t *shape);
@@ -151,6 +179,13 @@ ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V
                                      int32_t *idx_out, void *workspace,
                                      size_t workspace_bytes, const ds_shape_t *shape,
                                      void *stream);
+
+/* ds_sparse_decode over an interleaved cache KV [B, Hkv, L_max, 2, d]
+ * (DS_KV_INTERLEAVED); everything else as ds_sparse_decode. */
+ds_status_t ds_sparse_decode_kv(const void *q, const void *label, const void *KV,
+                                const int32_t *channels, float *out, int32_t *idx_out,
+                                void *workspace, size_t workspace_bytes,
+                                const ds_shape_t *shape, void *stream);
 
 /*
  * Dense decode attention over all L tokens (Sec. 2.1), the in-library

@@ -76,6 +76,22 @@ def build_label(K, channels, L):
     return label_write(K, channels, label, 0, L)
 
 
+def append_kv(k_new, v_new, K, V, channels, label, t0):
+    """Decode-step cache maintenance (Sec. 4.2): in place, the n new tokens' rows
+    k_new, v_new [B,Hkv,n,d] become tokens [t0, t0+n) of K and V, and their
+    channel values the same tokens of the label cache."""
+    n = k_new.shape[2]
+    assert t0 >= 0 and t0 + n <= K.shape[2]
+    K[:, :, t0:t0 + n] = k_new
+    V[:, :, t0:t0 + n] = v_new
+    return label_write(K, channels, label, t0, n)
+
+
+def interleave_kv(K, V):
+    """[B,Hkv,L_max,2,d]: each token's K row followed by its V row."""
+    return np.ascontiguousarray(np.stack([K, V], axis=3))
+
+
 def scores(q, label, channels, L, precision=64):
     """Alg. 1 steps 1-2: [B,Hkv,L] float64 approximate scores."""
     q = _u16(q, "q"); label = _u16(label, "label"); channels = _i32(channels)

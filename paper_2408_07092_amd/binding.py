@@ -19,11 +19,12 @@ LIB_PATH = os.path.join(_HERE, "libdsattn.so")
 DS_OK = 0
 DS_ERR_NULL, DS_ERR_SHAPE, DS_ERR_ALIGN, DS_ERR_WORKSPACE, DS_ERR_UNSUPPORTED, DS_ERR_HIP = -1, -2, -3, -4, -5, -6
 DS_CALIB_Q, DS_CALIB_K, DS_CALIB_QK = 0, 1, 2
+DS_KV_SPLIT, DS_KV_INTERLEAVED = 0, 1
 
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
     "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_sparse_decode_nolabel",
-    "ds_dense_decode", "ds_select",
+    "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
     "ds_tune_set", "ds_tune_get",
@@ -65,6 +66,9 @@ def lib() -> ctypes.CDLL:
         L.ds_workspace_init.argtypes = [vp, sz, vp]
         L.ds_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_sparse_decode_nolabel.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
+        L.ds_sparse_decode_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
+        L.ds_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, shp, i32, i32, ctypes.c_int, vp]
+        L.ds_build_label_kv.argtypes = [vp, vp, vp, shp, vp]
         L.ds_dense_decode.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_select.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_gather_rows_host.argtypes = [vp, vp, vp, vp, shp, vp]
@@ -171,6 +175,24 @@ def ds_sparse_decode_nolabel(q, K, V, channels, out, idx_out, workspace, shp: Ds
                                           _dp(idx_out), _dp(workspace),
                                           workspace.numel() * workspace.element_size(),
                                           ctypes.byref(shp), _stream(stream)), "ds_sparse_decode_nolabel")
+
+
+def ds_sparse_decode_kv(q, label, KV, channels, out, idx_out, workspace, shp: DsShape, stream=None):
+    _check(lib().ds_sparse_decode_kv(_dp(q), _dp(label), _dp(KV), _dp(channels), _dp(out),
+                                     _dp(idx_out), _dp(workspace),
+                                     workspace.numel() * workspace.element_size(),
+                                     ctypes.byref(shp), _stream(stream)), "ds_sparse_decode_kv")
+
+
+def ds_append_kv(k_new, v_new, K, V, channels, label, shp: DsShape, t0, n_new, layout=DS_KV_SPLIT, stream=None):
+    _check(lib().ds_append_kv(_dp(k_new), _dp(v_new), _dp(K), _dp(V), _dp(channels), _dp(label),
+                              ctypes.byref(shp), int(t0), int(n_new), int(layout), _stream(stream)),
+           "ds_append_kv")
+
+
+def ds_build_label_kv(KV, channels, label, shp: DsShape, stream=None):
+    _check(lib().ds_build_label_kv(_dp(KV), _dp(channels), _dp(label), ctypes.byref(shp), _stream(stream)),
+           "ds_build_label_kv")
 
 
 def ds_dense_decode(q, K, V, out, workspace, shp: DsShape, stream=None):

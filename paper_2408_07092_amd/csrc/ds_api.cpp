@@ -115,7 +115,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
     "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2",
-    "k_refine_attend"};
+    "k_refine_attend", "k_append_kv"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -250,6 +250,35 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
     return DS_OK;
 }
 
+ds_status_t ds_build_label_kv(const void *KV, const int32_t *channels, void *label,
+                              const ds_shape_t *shape, void *stream)
+{
+    ds_status_t st = check_label_args(KV, channels, label, shape);
+    if (st != DS_OK) return st;
+    if (shape->L < 1 || shape->L > shape->L_max) return DS_ERR_SHAPE;
+    DS_TRY(launch_label(KV, channels, label, *shape, 0, shape->L, (hipStream_t)stream, 2 * kD));
+    return DS_OK;
+}
+
+ds_status_t ds_append_kv(const void *k_new, const void *v_new, void *K, void *V,
+                         const int32_t *channels, void *label, const ds_shape_t *shape, int32_t t0,
+                         int32_t n_new, ds_kv_layout_t layout, void *stream)
+{
+    if (!k_new || !v_new) return DS_ERR_NULL;
+    if (layout != DS_KV_SPLIT && layout != DS_KV_INTERLEAVED) return DS_ERR_SHAPE;
+    if (layout == DS_KV_SPLIT && !V) return DS_ERR_NULL;
+    ds_status_t st = check_label_args(K, channels, label, shape);
+    if (st != DS_OK) return st;
+    if (t0 < 0 || n_new < 0 || (int64_t)t0 + n_new > shape->L_max) return DS_ERR_SHAPE;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || (layout == DS_KV_SPLIT && !aligned(V, 256)))
+        return DS_ERR_ALIGN;
+    const bool il = layout == DS_KV_INTERLEAVED;
+    void *Vp = il ? static_cast<void *>(static_cast<char *>(K) + kD * 2) : V;
+    DS_TRY(launch_append_kv(k_new, v_new, K, Vp, channels, label, *shape, t0, n_new, il ? 2 * kD : kD,
+                            (hipStream_t)stream));
+    return DS_OK;
+}
+
 size_t ds_workspace_bytes(const ds_shape_t *shape)
 {
     if (!shape) return 0;
@@ -303,7 +332,8 @@ static ds_status_t enqueue_select(const void *q, const void *label, const int32_
 static ds_status_t sparse_decode_impl(const void *q, const void *label, const void *K, const void *V,
                                       const int32_t *channels, float *out, int32_t *idx_out,
                                       void *workspace, size_t workspace_bytes,
-                                      const ds_shape_t *shape, void *stream, bool label_is_k)
+                                      const ds_shape_t *shape, void *stream, bool label_is_k,
+                                      int kv_stride = kD)
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
@@ -313,7 +343,7 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     FusedPlan f;
-    if (!label_is_k && make_fused_plan(*shape, p, &f)) {
+    if (!label_is_k && kv_stride == kD && make_fused_plan(*shape, p, &f)) {
         if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
@@ -322,12 +352,12 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
         // behind the attention over the rows that are selected either way
         DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, label_is_k));
-        DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st));
+        DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
         return DS_OK;
     }
     rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st, label_is_k);
     if (rc != DS_OK) return rc;
-    DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st));
+    DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
     return DS_OK;
 }
 
@@ -347,6 +377,19 @@ ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V
 {
     return sparse_decode_impl(q, K, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
                               stream, true);
+}
+
+ds_status_t ds_sparse_decode_kv(const void *q, const void *label, const void *KV,
+                                const int32_t *channels, float *out, int32_t *idx_out,
+                                void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                                void *stream)
+{
+    if (!KV) return DS_ERR_NULL;
+    // a row is addressed by a 32-bit byte offset inside its unit: 512-byte steps here
+    if (shape && (int64_t)shape->L_max * 4 * kD > 0xffffffffll) return DS_ERR_SHAPE;
+    const void *V = static_cast<const char *>(KV) + kD * 2;
+    return sparse_decode_impl(q, label, KV, V, channels, out, idx_out, workspace, workspace_bytes, shape,
+                              stream, false, 2 * kD);
 }
 
 ds_status_t ds_select(const void *q, const void *label, const int32_t *channels, int32_t *idx_out,

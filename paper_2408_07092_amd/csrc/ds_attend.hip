@@ -30,6 +30,7 @@ struct AttendArgs {
     float *out;
     UnitCtl *ctl_rw;
     int Hq, Hkv, G, L, L_max, key_stride, ch, n_ch, k, k_eff, n_rows;
+    int kv_stride;       // halves from one token's K (V) row to the next: d, or 2d when K|V interleave
     // k_refine_attend only
     uint2 *cand;         // [units][L] (key, token) of the keys in bin b*, unordered
     uint32_t *ndef;      // [units][n_ch] keys above bin b* per chunk
@@ -85,9 +86,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
         Vu = Ku + kD * 2;
         row_bytes = 4 * kD;
     } else {
-        Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
-        Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
-        row_bytes = 2 * kD;
+        Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * a.kv_stride);
+        Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * a.kv_stride);
+        row_bytes = 2 * a.kv_stride;
     }
 
     auto row_of = [&](int ri) { return (MODE == 0) ? sel[ri] : (MODE == 1) ? (t0 + ri) : ri; };
@@ -340,9 +341,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     }
 
     // ---- 2..4 per pass over the query group
-    const char *Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * kD);
-    const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * kD);
-    constexpr uint32_t row_bytes = 2 * kD;
+    const char *Ku = reinterpret_cast<const char *>(a.K + (size_t)u * a.L_max * a.kv_stride);
+    const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * a.kv_stride);
+    const uint32_t row_bytes = 2 * a.kv_stride;
     int n_sel = 0;
     // First the definite rows that fill whole rounds of the four wavefronts (64 rows a round);
     // the rest of them joins the selected candidates in one list, so that at most one round of
@@ -483,7 +484,7 @@ static void launch_attend_mode(int kid, const AttendArgs &a, dim3 grid, size_t s
 
 hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
-                                hipStream_t st)
+                                hipStream_t st, int kv_stride)
 {
     AttendArgs a{};
     a.q = static_cast<const _Float16 *>(q);
@@ -499,6 +500,7 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
     a.n_rows = 0;
+    a.kv_stride = kv_stride;
     launch_attend_mode<0>(KID_ATTEND, a, dim3(p.n_ch, p.units), (size_t)p.ch * sizeof(int), st);
     return hipGetLastError();
 }
@@ -520,7 +522,8 @@ bool refine_attend_ok(const Plan &p)
 }
 
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
-                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st)
+                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
+                                int kv_stride)
 {
     AttendArgs a{};
     a.q = static_cast<const _Float16 *>(q);
@@ -539,6 +542,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
     a.spin_limit = 1u << 21;
+    a.kv_stride = kv_stride;
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
     switch (pick_gt(a.G)) {
@@ -563,6 +567,7 @@ hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void
     a.out = out;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.ch = p.ch; a.n_ch = p.n_ch;
+    a.kv_stride = kD;
     launch_attend_mode<1>(KID_DENSE, a, dim3(p.n_ch, p.units), 0, st);
     return hipGetLastError();
 }

@@ -53,6 +53,7 @@ enum KernelId {
     KID_FUSED,
     KID_ATTEND2,
     KID_REFINE_ATTEND,
+    KID_APPEND_KV,
     KID_COUNT
 };
 
@@ -101,16 +102,20 @@ hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_sh
                           hipStream_t st);
 hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
-                                hipStream_t st);
+                                hipStream_t st, int kv_stride = kD);
 bool refine_attend_ok(const Plan &p);
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
-                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st);
+                                int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
+                                int kv_stride = kD);
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,
                               const DensePlan &p, const ds_shape_t &s, int n_rows, hipStream_t st);
 hipError_t launch_label(const void *K, const int32_t *channels, void *label, const ds_shape_t &s,
-                        int t0, int n, hipStream_t st);
+                        int t0, int n, hipStream_t st, int kv_stride = kD);
+hipError_t launch_append_kv(const void *k_new, const void *v_new, void *K, void *V,
+                            const int32_t *channels, void *label, const ds_shape_t &s, int t0, int n,
+                            int kv_stride, hipStream_t st);
 hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,
                               const ds_shape_t &s, hipStream_t st);
 hipError_t launch_fused(const void *q, const void *label, const void *K, const void *V,

@@ -6,11 +6,12 @@ namespace ds {
 
 // label[u, t, j] = K[u, t, channels[h, j]] for t in [t0, t0 + n): a bit copy.
 // One thread per label element; writes are contiguous, reads pick 2-byte
-// elements out of the 256-byte K rows.
+// elements out of the 256-byte K rows (kv_stride halves apart: d, or 2d when
+// each K row is followed by the token's V row).
 __global__ __launch_bounds__(kWG) void k_label(const uint16_t *__restrict__ K,
                                                const int32_t *__restrict__ channels,
                                                uint16_t *__restrict__ label, int Hkv, int L_max,
-                                               int r, int t0, int n)
+                                               int r, int t0, int n, int kv_stride)
 {
     __shared__ int ch_sh[kD];
     const int u = blockIdx.y, h = u % Hkv;
@@ -22,7 +23,37 @@ __global__ __launch_bounds__(kWG) void k_label(const uint16_t *__restrict__ K,
         const size_t t = t0 + e / r;
         const int j = (int)(e % r);
         const size_t row = (size_t)u * L_max + t;
-        label[row * r + j] = K[row * kD + ch_sh[j]];
+        label[row * r + j] = K[row * kv_stride + ch_sh[j]];
+    }
+}
+
+// Decode-step cache maintenance in one launch (Sec. 4.2: in decoding only the new tokens'
+// heavy-channel values are added to the label cache): the n new tokens' K and V rows go into
+// the caches at tokens [t0, t0 + n) and their r label values into the label cache.
+// 16 lanes move one 256-byte row; the label values are picked out of the new rows afterwards.
+__global__ __launch_bounds__(kWG) void k_append_kv(const uint4 *__restrict__ k_new,
+                                                   const uint4 *__restrict__ v_new, uint4 *K, uint4 *V,
+                                                   const int32_t *__restrict__ channels,
+                                                   uint16_t *__restrict__ label, int Hkv, int L_max,
+                                                   int r, int t0, int n, int kv_stride16)
+{
+    __shared__ int ch_sh[kD];
+    const int u = blockIdx.y, h = u % Hkv;
+    if (threadIdx.x < r) ch_sh[threadIdx.x] = channels[h * r + threadIdx.x];
+    __syncthreads();
+    const int p = threadIdx.x & 15;
+    for (int i = blockIdx.x * 16 + (threadIdx.x >> 4); i < n; i += gridDim.x * 16) {
+        const size_t src = ((size_t)u * n + i) * 16 + p;
+        const size_t dst = ((size_t)u * L_max + t0 + i) * kv_stride16 + p;
+        K[dst] = k_new[src];
+        V[dst] = v_new[src];
+    }
+    const uint16_t *kn = reinterpret_cast<const uint16_t *>(k_new);
+    const size_t total = (size_t)n * r;
+    for (size_t e = (size_t)blockIdx.x * kWG + threadIdx.x; e < total; e += (size_t)gridDim.x * kWG) {
+        const size_t i = e / r;
+        const int j = (int)(e % r);
+        label[((size_t)u * L_max + t0 + i) * r + j] = kn[((size_t)u * n + i) * kD + ch_sh[j]];
     }
 }
 
@@ -69,7 +100,7 @@ __global__ __launch_bounds__(kWG) void k_probe(const uint4 *__restrict__ src, si
 }
 
 hipError_t launch_label(const void *K, const int32_t *channels, void *label, const ds_shape_t &s,
-                        int t0, int n, hipStream_t st)
+                        int t0, int n, hipStream_t st, int kv_stride)
 {
     if (n <= 0) return hipSuccess;
     const size_t total = (size_t)n * s.r;
@@ -77,7 +108,21 @@ hipError_t launch_label(const void *K, const int32_t *channels, void *label, con
     if (blocks > 4096) blocks = 4096;
     DS_LAUNCH(KID_LABEL, k_label, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
                        static_cast<const uint16_t *>(K), channels, static_cast<uint16_t *>(label),
-                       s.Hkv, s.L_max, s.r, t0, n);
+                       s.Hkv, s.L_max, s.r, t0, n, kv_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_append_kv(const void *k_new, const void *v_new, void *K, void *V,
+                            const int32_t *channels, void *label, const ds_shape_t &s, int t0, int n,
+                            int kv_stride, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    size_t blocks = ((size_t)n + 15) / 16;
+    if (blocks > 2048) blocks = 2048;
+    DS_LAUNCH(KID_APPEND_KV, k_append_kv, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
+              static_cast<const uint4 *>(k_new), static_cast<const uint4 *>(v_new),
+              static_cast<uint4 *>(K), static_cast<uint4 *>(V), channels,
+              static_cast<uint16_t *>(label), s.Hkv, s.L_max, s.r, t0, n, kv_stride / 8);
     return hipGetLastError();
 }
 

@@ -332,6 +332,69 @@ def test_nolabel_rejects_bad_arguments_and_matches_label_path_bytes():
     assert float(out.abs().max()) == 0.0
 
 
+# ---------------------------------------------------------------- interleaved K|V cache, fused append
+@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", [
+    (2, 4, 4, 777, 800, 8, 50),
+    (1, 16, 2, 3000, 3072, 16, 200),     # GQA 8 on the matrix cores
+    (1, 2, 2, 9000, 9000, 8, 600),       # long enough for the refine-and-attend launch
+])
+def test_interleaved_cache_append_and_decode(B, Hq, Hkv, L, L_max, r, k):
+    """Prefill L - 5 tokens, append 3 + 2 with the fused append (both layouts),
+    decode over the interleaved cache: caches and label bit-exact against the
+    oracle's append, decode against the oracle on the separate K and V."""
+    rng = np.random.default_rng(L)
+    w = small_workload(B, Hq, Hkv, L, r, k)
+    t = make_layer_numpy(w, L_max=L_max)
+    q, K, V = t["q"], t["K"], t["V"]
+    ch = rand_channels(Hkv, 128, r, seed=L)
+    L0 = L - 5
+    # oracle: caches holding L0 tokens, then two appends
+    K_o, V_o = K.copy(), V.copy()
+    K_o[:, :, L0:] = 0; V_o[:, :, L0:] = 0
+    lab_o = O.build_label(K_o, ch, L0)
+    steps = [(L0, 3), (L0 + 3, 2)]
+    for t0, n in steps:
+        O.append_kv(K[:, :, t0:t0 + n].copy(), V[:, :, t0:t0 + n].copy(), K_o, V_o, ch, lab_o, t0)
+    # HIP path, separate layout
+    shp = ds.shape(B, Hq, Hkv, 128, L, L_max, r, k)
+    shp0 = ds.shape(B, Hq, Hkv, 128, L0, L_max, r, k)
+    K_d, V_d = to_dev(K_o * 0), to_dev(V_o * 0)
+    K_d[:, :, :L0] = to_dev(K[:, :, :L0]); V_d[:, :, :L0] = to_dev(V[:, :, :L0])
+    ch_d = to_dev(ch)
+    lab_d = torch.zeros((B, Hkv, L_max, r), dtype=torch.float16, device="cuda")
+    ds.ds_build_label(K_d, ch_d, lab_d, shp0)
+    # HIP path, interleaved layout
+    KV_d = torch.zeros((B, Hkv, L_max, 2, 128), dtype=torch.float16, device="cuda")
+    KV_d[:, :, :L0, 0] = K_d[:, :, :L0]; KV_d[:, :, :L0, 1] = V_d[:, :, :L0]
+    lab_i = torch.zeros_like(lab_d)
+    ds.ds_build_label_kv(KV_d, ch_d, lab_i, shp0)
+    for t0, n in steps:
+        kn, vn = to_dev(K[:, :, t0:t0 + n]), to_dev(V[:, :, t0:t0 + n])
+        ds.ds_append_kv(kn, vn, K_d, V_d, ch_d, lab_d, shp, t0, n, ds.DS_KV_SPLIT)
+        ds.ds_append_kv(kn, vn, KV_d, None, ch_d, lab_i, shp, t0, n, ds.DS_KV_INTERLEAVED)
+    torch.cuda.synchronize()
+    for got, want in ((K_d, K_o), (V_d, V_o), (lab_d, lab_o), (lab_i, lab_o),
+                      (KV_d, O.interleave_kv(K_o, V_o))):
+        assert np.array_equal(got.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    # decode over the interleaved cache
+    ws = ds.ds_workspace_alloc(shp)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda")
+    ds.ds_sparse_decode_kv(to_dev(q), lab_i, KV_d, ch_d, out, idx, ws, shp)
+    torch.cuda.synchronize()
+    ref_out, ref_idx = O.sparse_decode(q, lab_o, K_o, V_o, ch, L, k, precision=32)
+    check_index_structure(idx.cpu().numpy(), L, k)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    check_output(out.cpu().numpy(), ref_out, "interleaved decode")
+    # bad layout / range are refused before anything is enqueued
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_append_kv(to_dev(K[:, :, :2]), to_dev(V[:, :, :2]), K_d, V_d, ch_d, lab_d, shp, L_max - 1, 2)
+    assert e.value.status == ds.DS_ERR_SHAPE
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_append_kv(to_dev(K[:, :, :2]), to_dev(V[:, :, :2]), K_d, None, ch_d, lab_d, shp, 0, 2, ds.DS_KV_SPLIT)
+    assert e.value.status == ds.DS_ERR_NULL
+
+
 # ---------------------------------------------------------------- determinism across tuning-independent reruns
 def test_run_to_run_bytes_identical_c1_many_times():
     w = WORKLOADS["C1"]

@@ -127,6 +127,25 @@ def test_label_is_exact_channel_copy_and_append_equals_build():
     assert np.array_equal(lab.view(np.uint16), lab2.view(np.uint16))
 
 
+def test_append_kv_equals_cache_built_in_one_go():
+    """Appending the last tokens' rows to a shorter cache gives the bytes of the
+    cache that held them from the start, label cache included; decode results agree."""
+    q, K, V = small_case(d=16, L=37, L_max=40, seed=5)
+    ch = np.stack([np.sort(np.random.default_rng(h).permutation(16)[:4]) for h in range(4)]).astype(np.int32)
+    lab = O.build_label(K, ch, 37)
+    K2, V2 = K.copy(), V.copy()
+    K2[:, :, 30:] = 0; V2[:, :, 30:] = 0
+    lab2 = O.build_label(K2, ch, 30)
+    O.append_kv(K[:, :, 30:35].copy(), V[:, :, 30:35].copy(), K2, V2, ch, lab2, 30)
+    O.append_kv(K[:, :, 35:37].copy(), V[:, :, 35:37].copy(), K2, V2, ch, lab2, 35)
+    for a, b in ((K, K2), (V, V2), (lab, lab2)):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    kv = O.interleave_kv(K, V)
+    assert kv.shape == K.shape[:3] + (2, 16)
+    assert np.array_equal(kv[:, :, :, 0].view(np.uint16), K.view(np.uint16))
+    assert np.array_equal(kv[:, :, :, 1].view(np.uint16), V.view(np.uint16))
+
+
 # ---------------------------------------------------------------- approximate scores
 def test_scores_hand_case():
     # L = 4, r = 2, channels (3, 1): s_hat[t] = q[3]*K[t,3] + q[1]*K[t,1]

@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--tune", default="", help="knob=value,... (ds_tune_set)")
+    ap.add_argument("--interleaved", action="store_true",
+                    help="K|V cache as one [L,2,d] array per head (512-byte gathers), ds_sparse_decode_kv")
     ap.add_argument("--label-ablation", action="store_true",
                     help="with / without label cache over the batch x length grid of the paper's ablation table")
     return ap.parse_args()
@@ -95,7 +97,12 @@ def main():
         t = make_layer_torch(w, dev, layer=l)
         label = torch.empty((w.B, w.Hkv, w.L, w.r), dtype=torch.float16, device=dev)
         ds.ds_build_label(t["K"], ch, label, shp)
-        layers.append((t["q"], label, t["K"], t["V"], ch))
+        if args.interleaved:
+            KV = torch.stack((t["K"], t["V"]), dim=3).contiguous()
+            layers.append((t["q"], label, KV, None, ch))
+        else:
+            layers.append((t["q"], label, t["K"], t["V"], ch))
+        del t
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
     ws = ds.ds_workspace_alloc(shp, dev)
@@ -104,7 +111,10 @@ def main():
 
     def sparse_sweep():
         for (q, label, K, V, ch) in layers:
-            ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+            if V is None:
+                ds.ds_sparse_decode_kv(q, label, K, ch, out, None, ws, shp)
+            else:
+                ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
 
     def nolabel_sweep():
         for (q, label, K, V, ch) in layers:
@@ -185,10 +195,11 @@ def main():
         "ms_per_step": round(ms_step, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.note}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "L": w.L,
-                   "r": w.r, "k": w.k, "storage": "f16", "layers_per_step": n_layers, "hip_graph": use_graph},
+                   "r": w.r, "k": w.k, "storage": "f16", "layers_per_step": n_layers, "hip_graph": use_graph,
+                   "kv_layout": "interleaved [L,2,d]" if args.interleaved else "separate K, V [L,d]"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": counted_traffic(w.name, dom),
+                     "traffic": None if args.interleaved else counted_traffic(w.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
     }
     alg = w.algorithmic_bytes()
@@ -204,7 +215,7 @@ def main():
     }
 
     # ---- in-library dense decode on the same caches
-    if not args.no_dense:
+    if not args.no_dense and not args.interleaved:
         d_steps = max(2, args.steps // 4)
         d_ms, _ = timed(dense_sweep, d_steps, 1, use_graph)
         d_us = d_ms * 1e3 / n_layers
@@ -213,7 +224,7 @@ def main():
         extra["speedup_vs_dense"] = round(d_us / us_layer, 3)
 
     # ---- the same decode scoring straight from the K rows (what the label cache buys; Sec. 4.2)
-    if not args.no_dense:
+    if not args.no_dense and not args.interleaved:
         n_ms, _ = timed(nolabel_sweep, max(2, args.steps // 4), 1, use_graph)
         extra["nolabel_us_per_layer"] = round(n_ms * 1e3 / n_layers, 3)
         extra["label_cache_speedup"] = round(n_ms * 1e3 / n_layers / us_layer, 3)
@@ -226,6 +237,8 @@ def main():
             ds.ds_probe_stream_read(K, sink)
     p_ms, _ = timed(probe_sweep, max(2, args.steps // 4), 1, use_graph)
     extra["stream_read_ceiling_GBps"] = round(n_layers * layers[0][2].numel() * 2 / (p_ms * 1e-3) / 1e9, 1)
+    if args.interleaved:
+        args.no_cpu = True   # the oracle sample below reads the separate layout
 
     # ---- CPU oracle on the host cores, bounded sample
     if not args.no_cpu:

@@ -16,7 +16,8 @@
  *   - Layouts (row-major, element counts):
  *       q        [B, Hq, d]            fp16
  *       K, V     [B, Hkv, L_max, d]    fp16   (tokens 0..L-1 valid)
- *       label    [B, Hkv, L_max, r]    fp16
+ *       label    [B, Hkv, L_max, r]    fp16   (4-bit variant: codes [B, Hkv, L_max, ceil(r/8)] uint32
+ *                                      and amax [B, Hkv, r] float)
  *       channels [Hkv, r]              int32  (shared across batch)
  *       scores   [B, Hkv, L]           double
  *       idx      [B, Hkv, k]           int32  (first k_eff ascending, rest -1)
@@ -116,6 +117,111 @@ void ds_oracle_scores(const uint16_t *q, const uint16_t *label,
                     out[t] = acc;
                 }
             }
+        }
+}
+
+/* ---- Sec. 4.2, label cache kept in 4 bits ---------------------------------- */
+/* The paper states only that the label cache can be stored in 4-bit; the
+ * quantiser below is this build's reading (symmetric, one step size per batch
+ * entry, KV head and label channel, fixed when the cache is built):
+ *   amax[b,h,j] = max over t < L of |K[b,h,t,C[h,j]]|          (exact)
+ *   inv  = 7 / amax, step = amax / 7      (binary32 divisions; both 0 if amax = 0)
+ *   code[t,j] = clamp(rint((float)K[t,C[j]] * inv), -8, 7)      (binary32 product,
+ *               round half to even); the label value is code * step.
+ * Eight codes share a 32-bit word: channel j of a token sits in bits
+ * [4 (j mod 8), 4 (j mod 8) + 4) of the token's word j / 8 as a two's-complement
+ * nibble; nibbles past r are zero.  codes [B, Hkv, L_max, W], W = ceil(r / 8).
+ * Tokens appended later are coded with the amax of the build (they saturate
+ * at -8 / 7 if they exceed it).                                              */
+void ds_oracle_label_q4_amax(const uint16_t *K, const int32_t *channels, float *amax,
+                             int B, int Hkv, int L, int L_max, int d, int r)
+{
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h)
+            for (int j = 0; j < r; ++j) {
+                double m = 0.0;
+                for (int t = 0; t < L; ++t) {
+                    int64_t row = ((int64_t)b * Hkv + h) * L_max + t;
+                    double x = fabs(half_to_double(K[row * d + channels[h * r + j]]));
+                    if (x > m) m = x;
+                }
+                amax[((int64_t)b * Hkv + h) * r + j] = (float)m; /* exact: an fp16 value */
+            }
+}
+
+void ds_oracle_label_q4_write(const uint16_t *K, const int32_t *channels, const float *amax,
+                              uint32_t *codes, int B, int Hkv, int L_max, int d, int r,
+                              int t0, int n)
+{
+    int W = (r + 7) / 8;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h)
+            for (int t = t0; t < t0 + n; ++t) {
+                int64_t row = ((int64_t)b * Hkv + h) * L_max + t;
+                for (int w = 0; w < W; ++w) codes[row * W + w] = 0u;
+                for (int j = 0; j < r; ++j) {
+                    float a = amax[((int64_t)b * Hkv + h) * r + j];
+                    float inv = a > 0.0f ? 7.0f / a : 0.0f;
+                    float x = (float)half_to_double(K[row * d + channels[h * r + j]]);
+                    float y = rintf(x * inv);
+                    int c = y < -8.0f ? -8 : (y > 7.0f ? 7 : (int)y);
+                    codes[row * W + j / 8] |= ((uint32_t)c & 0xfu) << (4 * (j % 8));
+                }
+            }
+}
+
+static int q4_code(const uint32_t *codes_row, int j)
+{
+    int nib = (int)((codes_row[j / 8] >> (4 * (j % 8))) & 0xfu);
+    return nib >= 8 ? nib - 16 : nib;
+}
+
+/* Approximate scores from the 4-bit label cache:
+ *   s_hat[t] = sum_{g in group} sum_j q_g[C[j]] * (code[t,j] * step[j]).
+ * precision = 64: that sum in double (step is the stored binary32 value).
+ * precision = 32: binary32 in streaming order: w[j] = (sum_g (float)q_g[C[j]],
+ * g ascending) * step[j], then acc = fma(w[j], (float)code[t,j], acc), j ascending. */
+void ds_oracle_scores_q4(const uint16_t *q, const uint32_t *codes, const float *amax,
+                         const int32_t *channels, double *scores, int B, int Hq, int Hkv,
+                         int d, int L, int L_max, int r, int precision)
+{
+    int G = Hq / Hkv, W = (r + 7) / 8;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h) {
+            const uint32_t *cu = codes + ((int64_t)b * Hkv + h) * L_max * W;
+            const float *au = amax + ((int64_t)b * Hkv + h) * r;
+            double *out = scores + ((int64_t)b * Hkv + h) * L;
+            float *step = (float *)malloc(sizeof(float) * r);
+            float *wq = (float *)malloc(sizeof(float) * r);
+            for (int j = 0; j < r; ++j) {
+                step[j] = au[j] / 7.0f;
+                float a = 0.0f;
+                for (int g = 0; g < G; ++g) {
+                    const uint16_t *qg = q + ((int64_t)b * Hq + h * G + g) * d;
+                    a = a + (float)half_to_double(qg[channels[h * r + j]]);
+                }
+                wq[j] = a * step[j];
+            }
+            for (int t = 0; t < L; ++t) {
+                const uint32_t *row = cu + (int64_t)t * W;
+                if (precision == 32) {
+                    float acc = 0.0f;
+                    for (int j = 0; j < r; ++j) acc = fmaf(wq[j], (float)q4_code(row, j), acc);
+                    out[t] = (double)acc;
+                } else {
+                    double acc = 0.0;
+                    for (int g = 0; g < G; ++g) {
+                        const uint16_t *qg = q + ((int64_t)b * Hq + h * G + g) * d;
+                        for (int j = 0; j < r; ++j)
+                            acc += half_to_double(qg[channels[h * r + j]]) *
+                                   ((double)q4_code(row, j) * (double)step[j]);
+                    }
+                    out[t] = acc;
+                }
+            }
+            free(step);
+            free(wq);
         }
 }
 
@@ -244,6 +350,25 @@ void ds_oracle_sparse_decode(const uint16_t *q, const uint16_t *label,
     double *scores = scores_out ? scores_out
                                 : (double *)malloc(sizeof(double) * (size_t)(units * L));
     ds_oracle_scores(q, label, channels, scores, B, Hq, Hkv, d, L, L_max, r, precision);
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t u = 0; u < units; ++u)
+        ds_oracle_topk(scores + u * L, L, k, idx + u * k,
+                       sorted_out ? sorted_out + u * L : NULL);
+    ds_oracle_attend_idx(q, K, V, idx, out, B, Hq, Hkv, d, L_max, k);
+    if (!scores_out) free(scores);
+}
+
+/* Algorithm 1 with the scores taken from the 4-bit label cache. */
+void ds_oracle_sparse_decode_q4(const uint16_t *q, const uint32_t *codes, const float *amax,
+                                const uint16_t *K, const uint16_t *V, const int32_t *channels,
+                                double *out, int32_t *idx, double *scores_out,
+                                double *sorted_out, int B, int Hq, int Hkv, int d, int L,
+                                int L_max, int r, int k, int precision)
+{
+    int64_t units = (int64_t)B * Hkv;
+    double *scores = scores_out ? scores_out
+                                : (double *)malloc(sizeof(double) * (size_t)(units * L));
+    ds_oracle_scores_q4(q, codes, amax, channels, scores, B, Hq, Hkv, d, L, L_max, r, precision);
 #pragma omp parallel for schedule(dynamic)
     for (int64_t u = 0; u < units; ++u)
         ds_oracle_topk(scores + u * L, L, k, idx + u * k,

@@ -92,6 +92,64 @@ def interleave_kv(K, V):
     return np.ascontiguousarray(np.stack([K, V], axis=3))
 
 
+def label_q4_amax(K, channels, L):
+    """4-bit label cache (Sec. 4.2), step 1: amax[B,Hkv,r] float32 over tokens [0, L)."""
+    K = _u16(K, "K"); channels = _i32(channels)
+    B, Hkv, L_max, d = K.shape
+    r = channels.shape[1]
+    amax = np.zeros((B, Hkv, r), dtype=np.float32)
+    _load().ds_oracle_label_q4_amax(_p(K), _p(channels), _p(amax), B, Hkv, L, L_max, d, r)
+    return amax
+
+
+def label_q4_write(K, channels, amax, codes, t0, n):
+    """In place: codes[:, :, t0:t0+n] = the packed 4-bit codes of K's label channels."""
+    K = _u16(K, "K"); channels = _i32(channels)
+    B, Hkv, L_max, d = K.shape
+    r = channels.shape[1]
+    assert codes.dtype == np.uint32 and codes.flags.c_contiguous and codes.shape == (B, Hkv, L_max, (r + 7) // 8)
+    assert amax.dtype == np.float32 and amax.flags.c_contiguous and amax.shape == (B, Hkv, r)
+    assert 0 <= t0 and t0 + n <= L_max
+    _load().ds_oracle_label_q4_write(_p(K), _p(channels), _p(amax), _p(codes), B, Hkv, L_max, d, r, t0, n)
+    return codes
+
+
+def build_label_q4(K, channels, L):
+    """(codes [B,Hkv,L_max,ceil(r/8)] uint32, amax [B,Hkv,r] float32)."""
+    B, Hkv, L_max, _ = K.shape
+    r = np.asarray(channels).shape[1]
+    amax = label_q4_amax(K, channels, L)
+    codes = np.zeros((B, Hkv, L_max, (r + 7) // 8), dtype=np.uint32)
+    return label_q4_write(K, channels, amax, codes, 0, L), amax
+
+
+def scores_q4(q, codes, amax, channels, L, precision=64):
+    q = _u16(q, "q"); channels = _i32(channels)
+    B, Hq, d = q.shape
+    _, Hkv, L_max, _ = codes.shape
+    r = channels.shape[1]
+    out = np.empty((B, Hkv, L), dtype=np.float64)
+    _load().ds_oracle_scores_q4(_p(q), _p(codes), _p(amax), _p(channels), _p(out),
+                                B, Hq, Hkv, d, L, L_max, r, precision)
+    return out
+
+
+def sparse_decode_q4(q, codes, amax, K, V, channels, L, k, precision=64, want_scores=False):
+    """Algorithm 1 with scores from the 4-bit label cache; returns like sparse_decode."""
+    q = _u16(q, "q"); K = _u16(K, "K"); V = _u16(V, "V"); channels = _i32(channels)
+    B, Hq, d = q.shape
+    _, Hkv, L_max, _ = K.shape
+    r = channels.shape[1]
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    idx = np.empty((B, Hkv, k), dtype=np.int32)
+    sc = np.empty((B, Hkv, L), dtype=np.float64) if want_scores else None
+    srt = np.empty((B, Hkv, L), dtype=np.float64) if want_scores else None
+    _load().ds_oracle_sparse_decode_q4(_p(q), _p(codes), _p(amax), _p(K), _p(V), _p(channels), _p(out), _p(idx),
+                                       _p(sc) if want_scores else None, _p(srt) if want_scores else None,
+                                       B, Hq, Hkv, d, L, L_max, r, k, precision)
+    return (out, idx, sc, srt) if want_scores else (out, idx)
+
+
 def scores(q, label, channels, L, precision=64):
     """Alg. 1 steps 1-2: [B,Hkv,L] float64 approximate scores."""
     q = _u16(q, "q"); label = _u16(label, "label"); channels = _i32(channels)

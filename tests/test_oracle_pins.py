@@ -146,6 +146,102 @@ def test_append_kv_equals_cache_built_in_one_go():
     assert np.array_equal(kv[:, :, :, 1].view(np.uint16), V.view(np.uint16))
 
 
+# ---------------------------------------------------------------- 4-bit label cache
+def _unpack_q4(codes, r):
+    """numpy view of the packed codes as int [.., r] (independent of the oracle's unpacking)."""
+    out = np.empty(codes.shape[:-1] + (r,), dtype=np.int64)
+    for j in range(r):
+        nib = (codes[..., j // 8] >> np.uint32(4 * (j % 8))) & np.uint32(15)
+        out[..., j] = np.where(nib >= 8, nib.astype(np.int64) - 16, nib.astype(np.int64))
+    return out
+
+
+def test_q4_hand_case_codes_and_packing():
+    # one unit, r = 3 channels (5, 0, 2), four tokens, amax = 7, 3.5, 0 -> steps 1, 0.5, 0
+    K = np.zeros((1, 1, 5, 8), np.float16)
+    K[0, 0, :4, 5] = [7, -7, 2.5, -3.5]        # x*inv = x: 2.5 -> 2 and -3.5 -> -4 (half to even)
+    K[0, 0, :4, 0] = [3.5, 0.25, -0.75, 1.0]   # x*inv = 2x: 7, 0.5 -> 0, -1.5 -> -2, 2
+    ch = np.array([[5, 0, 2]], np.int32)
+    codes, amax = O.build_label_q4(K, ch, 4)
+    assert amax.tolist() == [[[7.0, 3.5, 0.0]]]
+    want = np.array([[7, 7, 0], [-7, 0, 0], [2, -2, 0], [-4, 2, 0]])
+    assert np.array_equal(_unpack_q4(codes, 3)[0, 0, :4], want)
+    assert codes.shape == (1, 1, 5, 1) and not codes[0, 0, 4].any()
+    # packing: channel j in bits [4j, 4j+4), two's complement; unused nibbles zero
+    assert int(codes[0, 0, 1, 0]) == ((-7) & 15) | (0 << 4)
+    assert int(codes[0, 0, 3, 0]) == ((-4) & 15) | (2 << 4)
+    # an appended token beyond amax saturates at -8 / 7 under the frozen amax
+    K[0, 0, 4, 5], K[0, 0, 4, 0] = -100.0, 100.0
+    O.label_q4_write(K, ch, amax, codes, 4, 1)
+    assert _unpack_q4(codes, 3)[0, 0, 4].tolist() == [-8, 7, 0]
+
+
+@pytest.mark.parametrize("r", [1, 8, 11, 16])
+def test_q4_quantiser_error_bound_range_and_scale_equivariance(r):
+    q, K, V = small_case(d=32, L=61, L_max=64, seed=r)
+    rng = np.random.default_rng(r)
+    ch = np.stack([rng.permutation(32)[:r] for _ in range(4)]).astype(np.int32)
+    codes, amax = O.build_label_q4(K, ch, 61)
+    c = _unpack_q4(codes, r)
+    assert c.min() >= -8 and c.max() <= 7
+    lab = np.stack([K[:, h][..., ch[h]] for h in range(4)], axis=1).astype(np.float64)   # [B,Hkv,L_max,r]
+    assert np.array_equal(amax, np.abs(lab[:, :, :61]).max(axis=2).astype(np.float32))
+    step = (amax / np.float32(7.0)).astype(np.float64)[:, :, None, :]
+    err = np.abs(c[:, :, :61] * step - lab[:, :, :61])
+    assert (err <= 0.5 * step * (1 + 1e-6)).all()          # nearest code; never further than half a step
+    assert (np.abs(c[:, :, :61]).max(axis=2) == 7).all()    # the largest element of a channel maps to +-7
+    assert not codes[:, :, 61:].any()
+    # doubling K doubles amax and leaves every code unchanged (power-of-two scaling is exact)
+    codes2, amax2 = O.build_label_q4((K * np.float16(2)).astype(np.float16), ch, 61)
+    assert np.array_equal(amax2, amax * 2) and np.array_equal(codes2, codes)
+    # append == build
+    codes3 = np.zeros_like(codes)
+    O.label_q4_write(K, ch, amax, codes3, 0, 40)
+    O.label_q4_write(K, ch, amax, codes3, 40, 21)
+    assert np.array_equal(codes3, codes)
+
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_q4_scores_equal_numpy_on_dequantised_labels_and_binary32_order(G):
+    q, K, V = small_case(Hq=4 * G, d=32, L=50, L_max=50, seed=7 + G)
+    ch = np.stack([np.sort(np.random.default_rng(h).permutation(32)[:8]) for h in range(4)]).astype(np.int32)
+    codes, amax = O.build_label_q4(K, ch, 50)
+    c = _unpack_q4(codes, 8).astype(np.float64)
+    step32 = amax / np.float32(7.0)
+    deq = c * step32.astype(np.float64)[:, :, None, :]
+    s64 = O.scores_q4(q, codes, amax, ch, 50, precision=64)
+    s32 = O.scores_q4(q, codes, amax, ch, 50, precision=32)
+    for b in range(2):
+        for h in range(4):
+            qg = q[b, h * G:(h + 1) * G][:, ch[h]].astype(np.float64)           # [G, r]
+            np.testing.assert_allclose(s64[b, h], deq[b, h] @ qg.sum(0), rtol=1e-12, atol=1e-12)
+            # binary32 mode: w_j = (sum_g q_g[C_j]) * step_j in float32, then sequential fma
+            w = np.zeros(8, np.float32)
+            for g in range(G):
+                w = w + q[b, h * G + g][ch[h]].astype(np.float32)
+            w = w * step32[b, h]
+            for t in (0, 17, 49):
+                acc = np.float32(0)
+                for j in range(8):   # products of a float32 and a small integer: fma == exact product, then one rounding
+                    acc = np.float32(np.float64(w[j]) * c[b, h, t, j] + np.float64(acc))
+                assert s32[b, h, t] == np.float64(acc)
+
+
+def test_q4_sparse_decode_is_topk_of_q4_scores_then_exact_attention_and_k_ge_L_is_dense():
+    q, K, V = small_case(d=32, L=64, L_max=64, seed=21)
+    ch = np.stack([np.sort(np.random.default_rng(h + 9).permutation(32)[:8]) for h in range(4)]).astype(np.int32)
+    codes, amax = O.build_label_q4(K, ch, 64)
+    out, idx, sc, srt = O.sparse_decode_q4(q, codes, amax, K, V, ch, 64, 9, want_scores=True)
+    assert np.array_equal(sc, O.scores_q4(q, codes, amax, ch, 64))
+    for b in range(2):
+        for h in range(4):
+            want = np.sort(np.lexsort((np.arange(64), -sc[b, h]))[:9])
+            assert np.array_equal(idx[b, h], want)
+    np.testing.assert_allclose(out, O.attend_idx(q, K, V, idx), rtol=0, atol=0)
+    out_all, _ = O.sparse_decode_q4(q, codes, amax, K, V, ch, 64, 64)
+    np.testing.assert_allclose(out_all, np_dense(q, K, V, 64), atol=1e-12)
+
+
 # ---------------------------------------------------------------- approximate scores
 def test_scores_hand_case():
     # L = 4, r = 2, channels (3, 1): s_hat[t] = q[3]*K[t,3] + q[1]*K[t,1]

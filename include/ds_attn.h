@@ -139,6 +139,27 @@ ds_status_t ds_append_kv(const void *k_new, const void *v_new, void *K, void *V,
 ds_status_t ds_build_label_kv(const void *KV, const int32_t *channels, void *label,
                               const ds_shape_t *shape, void *stream);
 
+/*
+ * Label cache kept in 4 bits (Sec. 4.2 says the label cache can be stored in
+ * 4-bit and gives no quantiser; this one is symmetric with one step per batch
+ * entry, KV head and label channel, fixed when the cache is built):
+ *   amax[b, h, j]  = max over t < L of |K[b, h, t, channels[h, j]]|
+ *   code[t, j]     = clamp(rint(K[t, channels[j]] * (7 / amax[j])), -8, 7)
+ *                    (binary32 product of the binary32 quotient, half to even)
+ *   label value    = code * (amax / 7)
+ * label_q4 [B, Hkv, L_max, ceil(r/8)] uint32: channel j of a token is the
+ * two's-complement nibble in bits [4 (j mod 8), +4) of the token's word j / 8,
+ * nibbles past r are zero; amax [B, Hkv, r] fp32.  DEVICE pointers.
+ * ds_build_label_q4 computes amax over tokens [0, L) and codes them;
+ * ds_append_label_q4 codes tokens [t0, t0 + n_new) with the amax given (values
+ * beyond it saturate).  Argument checks as ds_build_label / ds_append_label.
+ */
+ds_status_t ds_build_label_q4(const void *K, const int32_t *channels, void *label_q4,
+                              float *amax, const ds_shape_t *shape, void *stream);
+ds_status_t ds_append_label_q4(const void *K, const int32_t *channels, void *label_q4,
+                               const float *amax, const ds_shape_t *shape, int32_t t0,
+                               int32_t n_new, void *stream);
+
 /* Bytes of workspace any decode/select/attend call with this shape needs
  * (a multiple of 256).  Pure host function; 0 if the shape is invalid. */
 size_t ds_workspace_bytes(const ds_shape_t *shape);
@@ -179,6 +200,18 @@ ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V
                                      int32_t *idx_out, void *workspace,
                                      size_t workspace_bytes, const ds_shape_t *shape,
                                      void *stream);
+
+/*
+ * ds_sparse_decode with the approximate scores taken from the 4-bit label cache:
+ *   s_hat[t] = sum_j w[j] * code[t, j],  w[j] = (sum_{g in group} q_g[channels[j]]) * (amax[j] / 7)
+ * in binary32 (g ascending, then fma over j ascending from 0); steps 3-5 of
+ * Algorithm 1 are unchanged (exact attention over the k selected fp16 rows).
+ */
+ds_status_t ds_sparse_decode_q4(const void *q, const void *label_q4, const float *amax,
+                                const void *K, const void *V, const int32_t *channels,
+                                float *out, int32_t *idx_out, void *workspace,
+                                size_t workspace_bytes, const ds_shape_t *shape,
+                                void *stream);
 
 /* ds_sparse_decode over an interleaved cache KV [B, Hkv, L_max, 2, d]
  * (DS_KV_INTERLEAVED); everything else as ds_sparse_decode. */

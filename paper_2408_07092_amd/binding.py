@@ -24,7 +24,8 @@ DS_KV_SPLIT, DS_KV_INTERLEAVED = 0, 1
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
     "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_sparse_decode_nolabel",
-    "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_dense_decode", "ds_select",
+    "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_build_label_q4",
+    "ds_append_label_q4", "ds_sparse_decode_q4", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
     "ds_tune_set", "ds_tune_get",
@@ -69,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.ds_sparse_decode_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, shp, i32, i32, ctypes.c_int, vp]
         L.ds_build_label_kv.argtypes = [vp, vp, vp, shp, vp]
+        L.ds_build_label_q4.argtypes = [vp, vp, vp, vp, shp, vp]
+        L.ds_append_label_q4.argtypes = [vp, vp, vp, vp, shp, i32, i32, vp]
+        L.ds_sparse_decode_q4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_dense_decode.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_select.argtypes = [vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_gather_rows_host.argtypes = [vp, vp, vp, vp, shp, vp]
@@ -193,6 +197,23 @@ def ds_append_kv(k_new, v_new, K, V, channels, label, shp: DsShape, t0, n_new, l
 def ds_build_label_kv(KV, channels, label, shp: DsShape, stream=None):
     _check(lib().ds_build_label_kv(_dp(KV), _dp(channels), _dp(label), ctypes.byref(shp), _stream(stream)),
            "ds_build_label_kv")
+
+
+def ds_build_label_q4(K, channels, label_q4, amax, shp: DsShape, stream=None):
+    _check(lib().ds_build_label_q4(_dp(K), _dp(channels), _dp(label_q4), _dp(amax), ctypes.byref(shp),
+                                   _stream(stream)), "ds_build_label_q4")
+
+
+def ds_append_label_q4(K, channels, label_q4, amax, shp: DsShape, t0, n_new, stream=None):
+    _check(lib().ds_append_label_q4(_dp(K), _dp(channels), _dp(label_q4), _dp(amax), ctypes.byref(shp),
+                                    int(t0), int(n_new), _stream(stream)), "ds_append_label_q4")
+
+
+def ds_sparse_decode_q4(q, label_q4, amax, K, V, channels, out, idx_out, workspace, shp: DsShape, stream=None):
+    _check(lib().ds_sparse_decode_q4(_dp(q), _dp(label_q4), _dp(amax), _dp(K), _dp(V), _dp(channels),
+                                     _dp(out), _dp(idx_out), _dp(workspace),
+                                     workspace.numel() * workspace.element_size(),
+                                     ctypes.byref(shp), _stream(stream)), "ds_sparse_decode_q4")
 
 
 def ds_dense_decode(q, K, V, out, workspace, shp: DsShape, stream=None):

@@ -115,7 +115,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
     "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2",
-    "k_refine_attend", "k_append_kv"};
+    "k_refine_attend", "k_append_kv", "k_q4_amax", "k_q4_write"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -250,6 +250,31 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
     return DS_OK;
 }
 
+ds_status_t ds_build_label_q4(const void *K, const int32_t *channels, void *label_q4, float *amax,
+                              const ds_shape_t *shape, void *stream)
+{
+    if (!amax) return DS_ERR_NULL;
+    ds_status_t st = check_label_args(K, channels, label_q4, shape);
+    if (st != DS_OK) return st;
+    if (shape->L < 1 || shape->L > shape->L_max) return DS_ERR_SHAPE;
+    if (!aligned(amax, 4)) return DS_ERR_ALIGN;
+    DS_TRY(launch_q4_amax(K, channels, amax, *shape, (hipStream_t)stream));
+    DS_TRY(launch_q4_write(K, channels, amax, label_q4, *shape, 0, shape->L, (hipStream_t)stream));
+    return DS_OK;
+}
+
+ds_status_t ds_append_label_q4(const void *K, const int32_t *channels, void *label_q4,
+                               const float *amax, const ds_shape_t *shape, int32_t t0,
+                               int32_t n_new, void *stream)
+{
+    if (!amax) return DS_ERR_NULL;
+    ds_status_t st = check_label_args(K, channels, label_q4, shape);
+    if (st != DS_OK) return st;
+    if (t0 < 0 || n_new < 0 || (int64_t)t0 + n_new > shape->L_max) return DS_ERR_SHAPE;
+    DS_TRY(launch_q4_write(K, channels, amax, label_q4, *shape, t0, n_new, (hipStream_t)stream));
+    return DS_OK;
+}
+
 ds_status_t ds_build_label_kv(const void *KV, const int32_t *channels, void *label,
                               const ds_shape_t *shape, void *stream)
 {
@@ -316,23 +341,23 @@ static ds_status_t select_common(const void *q, const void *label, const int32_t
 
 static ds_status_t enqueue_select(const void *q, const void *label, const int32_t *channels,
                                   void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
-                                  hipStream_t st, bool label_is_k = false)
+                                  hipStream_t st, ScoreSrc src = ScoreSrc())
 {
     // Units of up to 8K tokens: the scoring launch's last workgroup per unit also settles the
     // exact threshold (knob 4 = 1 forces the separate candidate launch, 2 forces the tail).
     const int mode = tune_get(4);
     const bool tail_refine = mode == 2 || (mode == 0 && s.L <= (1 << 13));
-    DS_TRY(launch_score(q, label, channels, ws, p, s, tail_refine, want_offsets, st, label_is_k));
+    DS_TRY(launch_score(q, label, channels, ws, p, s, tail_refine, want_offsets, st, src));
     if (!tail_refine) DS_TRY(launch_cand(ws, p, s, want_offsets, st));
     return DS_OK;
 }
 
-// ds_sparse_decode with the scores taken either from the label cache or (label_is_k) from the K
-// rows themselves.
+// ds_sparse_decode with the scores taken from the label cache, from the K rows themselves or from
+// the 4-bit label cache (`label` is then that source's array).
 static ds_status_t sparse_decode_impl(const void *q, const void *label, const void *K, const void *V,
                                       const int32_t *channels, float *out, int32_t *idx_out,
                                       void *workspace, size_t workspace_bytes,
-                                      const ds_shape_t *shape, void *stream, bool label_is_k,
+                                      const ds_shape_t *shape, void *stream, ScoreSrc src,
                                       int kv_stride = kD)
 {
     if (!K || !V || !out) return DS_ERR_NULL;
@@ -343,7 +368,7 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     FusedPlan f;
-    if (!label_is_k && kv_stride == kD && make_fused_plan(*shape, p, &f)) {
+    if (src.kind == SRC_LABEL && kv_stride == kD && make_fused_plan(*shape, p, &f)) {
         if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
@@ -351,11 +376,11 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     if (p.refine_attend && refine_attend_ok(p)) {
         // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
         // behind the attention over the rows that are selected either way
-        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, label_is_k));
+        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, src));
         DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
         return DS_OK;
     }
-    rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st, label_is_k);
+    rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st, src);
     if (rc != DS_OK) return rc;
     DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
     return DS_OK;
@@ -367,7 +392,7 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
                              void *stream)
 {
     return sparse_decode_impl(q, label, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
-                              stream, false);
+                              stream, ScoreSrc());
 }
 
 ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V,
@@ -375,8 +400,24 @@ ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V
                                      void *workspace, size_t workspace_bytes,
                                      const ds_shape_t *shape, void *stream)
 {
+    ScoreSrc src;
+    src.kind = SRC_K_ROWS;
     return sparse_decode_impl(q, K, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
-                              stream, true);
+                              stream, src);
+}
+
+ds_status_t ds_sparse_decode_q4(const void *q, const void *label_q4, const float *amax, const void *K,
+                                const void *V, const int32_t *channels, float *out,
+                                int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                                const ds_shape_t *shape, void *stream)
+{
+    if (!amax) return DS_ERR_NULL;
+    if (!aligned(amax, 4)) return DS_ERR_ALIGN;
+    ScoreSrc src;
+    src.kind = SRC_Q4;
+    src.amax = amax;
+    return sparse_decode_impl(q, label_q4, K, V, channels, out, idx_out, workspace, workspace_bytes,
+                              shape, stream, src);
 }
 
 ds_status_t ds_sparse_decode_kv(const void *q, const void *label, const void *KV,
@@ -389,7 +430,7 @@ ds_status_t ds_sparse_decode_kv(const void *q, const void *label, const void *KV
     if (shape && (int64_t)shape->L_max * 4 * kD > 0xffffffffll) return DS_ERR_SHAPE;
     const void *V = static_cast<const char *>(KV) + kD * 2;
     return sparse_decode_impl(q, label, KV, V, channels, out, idx_out, workspace, workspace_bytes, shape,
-                              stream, false, 2 * kD);
+                              stream, ScoreSrc(), 2 * kD);
 }
 
 ds_status_t ds_select(const void *q, const void *label, const int32_t *channels, int32_t *idx_out,

@@ -54,6 +54,8 @@ enum KernelId {
     KID_ATTEND2,
     KID_REFINE_ATTEND,
     KID_APPEND_KV,
+    KID_Q4_AMAX,
+    KID_Q4_WRITE,
     KID_COUNT
 };
 
@@ -81,6 +83,14 @@ struct DensePlan {
     size_t off_ctl, off_part, total;  // same control prefix as Plan
 };
 
+// Where the approximate scores come from: the fp16 label cache, the K rows themselves (no label
+// cache), or the 4-bit label cache (packed codes + per-channel amax).
+enum ScoreSrcKind { SRC_LABEL = 0, SRC_K_ROWS = 1, SRC_Q4 = 2 };
+struct ScoreSrc {
+    ScoreSrcKind kind = SRC_LABEL;
+    const float *amax = nullptr;  // SRC_Q4: [units][r]
+};
+
 bool make_plan(const ds_shape_t &s, Plan *p);
 bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);
 bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f);
@@ -95,7 +105,7 @@ bool prof_events(int id, hipEvent_t *start, hipEvent_t *stop);
 hipError_t launch_init(void *ws, size_t bytes, hipStream_t st);
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
                         const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
-                        hipStream_t st, bool label_is_k = false);
+                        hipStream_t st, ScoreSrc src = ScoreSrc());
 hipError_t launch_cand(void *ws, const Plan &p, const ds_shape_t &s, bool want_offsets,
                        hipStream_t st);
 hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_shape_t &s,
@@ -113,6 +123,10 @@ hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, floa
                               const DensePlan &p, const ds_shape_t &s, int n_rows, hipStream_t st);
 hipError_t launch_label(const void *K, const int32_t *channels, void *label, const ds_shape_t &s,
                         int t0, int n, hipStream_t st, int kv_stride = kD);
+hipError_t launch_q4_amax(const void *K, const int32_t *channels, float *amax, const ds_shape_t &s,
+                          hipStream_t st);
+hipError_t launch_q4_write(const void *K, const int32_t *channels, const float *amax, void *codes,
+                           const ds_shape_t &s, int t0, int n, hipStream_t st);
 hipError_t launch_append_kv(const void *k_new, const void *v_new, void *K, void *V,
                             const int32_t *channels, void *label, const ds_shape_t &s, int t0, int n,
                             int kv_stride, hipStream_t st);

@@ -1,5 +1,7 @@
 // Label-cache maintenance (Sec. 4.2), the host-row gather of the offload
 // arrangement (Sec. 5.1) and the read-bandwidth probe.
+#include <algorithm>
+
 #include "ds_device.h"
 
 namespace ds {
@@ -57,6 +59,74 @@ __global__ __launch_bounds__(kWG) void k_append_kv(const uint4 *__restrict__ k_n
     }
 }
 
+// ---------------------------------------------------------------- 4-bit label cache (Sec. 4.2)
+// The paper says only that the label cache can be kept in 4 bits.  Quantiser used here:
+// symmetric, one step per (unit, label channel), fixed at build time:
+//   amax[u, j] = max_t |K[u, t, C[j]]|,  code = clamp(rint(x * (7 / amax)), -8, 7),
+//   label value = code * (amax / 7); eight two's-complement nibbles per 32-bit word,
+//   channel j of a token in bits [4 (j mod 8), +4) of the token's word j / 8.
+// k_q4_amax: non-negative binary32 values order like their bit patterns, so the maximum is an
+// integer atomicMax (exact, order-free).  amax must be zero on entry.
+__global__ __launch_bounds__(kWG) void k_q4_zero(uint32_t *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * kWG + threadIdx.x; i < n; i += (size_t)gridDim.x * kWG) p[i] = 0u;
+}
+
+__global__ __launch_bounds__(kWG) void k_q4_amax(const _Float16 *__restrict__ K,
+                                                 const int32_t *__restrict__ channels,
+                                                 uint32_t *amax_bits, int Hkv, int L_max, int r, int n)
+{
+    __shared__ int ch_sh[kD];
+    __shared__ uint32_t mx_sh[kD];
+    const int u = blockIdx.y, h = u % Hkv;
+    if (threadIdx.x < kD) {
+        mx_sh[threadIdx.x] = 0u;
+        if (threadIdx.x < r) ch_sh[threadIdx.x] = channels[h * r + threadIdx.x];
+    }
+    __syncthreads();
+    const size_t total = (size_t)n * r;
+    for (size_t e = (size_t)blockIdx.x * kWG + threadIdx.x; e < total; e += (size_t)gridDim.x * kWG) {
+        const size_t t = e / r;
+        const int j = (int)(e % r);
+        const float x = __builtin_fabsf((float)K[((size_t)u * L_max + t) * kD + ch_sh[j]]);
+        atomicMax(&mx_sh[j], __float_as_uint(x));
+    }
+    __syncthreads();
+    if (threadIdx.x < r && mx_sh[threadIdx.x]) atomicMax(&amax_bits[(size_t)u * r + threadIdx.x], mx_sh[threadIdx.x]);
+}
+
+// One thread per (token, word): up to eight codes packed into the word.
+__global__ __launch_bounds__(kWG) void k_q4_write(const _Float16 *__restrict__ K,
+                                                  const int32_t *__restrict__ channels,
+                                                  const float *__restrict__ amax,
+                                                  uint32_t *__restrict__ codes, int Hkv, int L_max,
+                                                  int r, int t0, int n)
+{
+    __shared__ int ch_sh[kD];
+    __shared__ float inv_sh[kD];
+    const int u = blockIdx.y, h = u % Hkv;
+    if (threadIdx.x < r) {
+        ch_sh[threadIdx.x] = channels[h * r + threadIdx.x];
+        const float a = amax[(size_t)u * r + threadIdx.x];
+        inv_sh[threadIdx.x] = a > 0.0f ? 7.0f / a : 0.0f;
+    }
+    __syncthreads();
+    const int W = (r + 7) / 8;
+    const size_t total = (size_t)n * W;
+    for (size_t e = (size_t)blockIdx.x * kWG + threadIdx.x; e < total; e += (size_t)gridDim.x * kWG) {
+        const size_t row = (size_t)u * L_max + t0 + e / W;
+        const int w = (int)(e % W);
+        uint32_t word = 0u;
+        for (int i = 0; i < 8 && w * 8 + i < r; ++i) {
+            const int j = w * 8 + i;
+            const float y = __builtin_rintf((float)K[row * kD + ch_sh[j]] * inv_sh[j]);
+            const int c = y < -8.0f ? -8 : (y > 7.0f ? 7 : (int)y);
+            word |= ((uint32_t)c & 0xfu) << (4 * i);
+        }
+        codes[row * W + w] = word;
+    }
+}
+
 // rows[u, i, 0, :] = K_host[u, idx[u, i], :], rows[u, i, 1, :] = V_host[...]:
 // 16 lanes move one 256-byte row; K_host / V_host are pinned host memory read
 // over the host link by the kernel itself.
@@ -109,6 +179,34 @@ hipError_t launch_label(const void *K, const int32_t *channels, void *label, con
     DS_LAUNCH(KID_LABEL, k_label, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
                        static_cast<const uint16_t *>(K), channels, static_cast<uint16_t *>(label),
                        s.Hkv, s.L_max, s.r, t0, n, kv_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_q4_amax(const void *K, const int32_t *channels, float *amax, const ds_shape_t &s,
+                          hipStream_t st)
+{
+    const size_t n_amax = (size_t)s.B * s.Hkv * s.r;
+    hipLaunchKernelGGL(k_q4_zero, dim3((unsigned)std::min<size_t>((n_amax + kWG - 1) / kWG, 1024)), dim3(kWG),
+                       0, st, reinterpret_cast<uint32_t *>(amax), n_amax);
+    const size_t total = (size_t)s.L * s.r;
+    size_t blocks = (total + kWG * 8 - 1) / (kWG * 8);
+    if (blocks > 1024) blocks = 1024;
+    DS_LAUNCH(KID_Q4_AMAX, k_q4_amax, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
+              static_cast<const _Float16 *>(K), channels, reinterpret_cast<uint32_t *>(amax), s.Hkv,
+              s.L_max, s.r, s.L);
+    return hipGetLastError();
+}
+
+hipError_t launch_q4_write(const void *K, const int32_t *channels, const float *amax, void *codes,
+                           const ds_shape_t &s, int t0, int n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    const size_t total = (size_t)n * ((s.r + 7) / 8);
+    size_t blocks = (total + kWG - 1) / kWG;
+    if (blocks > 4096) blocks = 4096;
+    DS_LAUNCH(KID_Q4_WRITE, k_q4_write, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
+              static_cast<const _Float16 *>(K), channels, amax, static_cast<uint32_t *>(codes), s.Hkv,
+              s.L_max, s.r, t0, n);
     return hipGetLastError();
 }
 

@@ -34,6 +34,9 @@ __global__ __launch_bounds__(kWG) void k_init(uint4 *p, size_t n16)
 // RMODE -2: no label cache -- `label` is the K cache itself and the r channels of a token are
 // picked out of its 256-byte row, the access pattern the label cache exists to avoid (Sec. 4.2,
 // ablation in the appendix "Forward without Label Cache").  Same arithmetic, same keys.
+// RMODE -3: 4-bit label cache -- `label` holds packed codes (eight nibbles per 32-bit word,
+// ceil(r/8) words per token) and the label query carries the channel's step:
+// w[j] = (sum_g q_g[C[j]]) * (amax[j] / 7), acc = fma(w[j], code[t,j], acc), j ascending.
 template <int RMODE>
 __device__ __forceinline__ float label_dot(const _Float16 *__restrict__ row, const float *qs, int r)
 {
@@ -54,6 +57,7 @@ template <int RMODE>
 __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                                                const _Float16 *__restrict__ label,
                                                const int32_t *__restrict__ channels,
+                                               const float *__restrict__ amax,
                                                uint32_t *__restrict__ keys, uint32_t *hist,
                                                uint32_t *coarse, UnitCtl *ctl, uint32_t *offs, int Hq, int Hkv,
                                                int G, int L, int L_max, int r, int key_stride, int sc_chunk,
@@ -116,6 +120,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
             for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
     }
     if (tid < r) {
+        if constexpr (RMODE == -3) a_q = a_q * (amax[(size_t)u * r + tid] / 7.0f);
         qs_sh[tid] = a_q;
         ch_sh[tid] = c_q;
     }
@@ -143,6 +148,52 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
             }
             t0 += kWG * UNR;
             if (t0 < t_end) issue(t0);
+        }
+    } else if constexpr (RMODE == -3) {
+        const int W = (r + 7) / 8;
+        const uint32_t *cu = reinterpret_cast<const uint32_t *>(label) + (size_t)u * L_max * W;
+        auto nib = [](uint32_t word, int i) { return (float)(((int32_t)(word << (28 - 4 * i))) >> 28); };
+        if (W == 1 && (L_max & 3) == 0) {
+            // four tokens per 16-byte load, four loads in flight; r <= 8 with w[j] = 0 beyond r
+            // (a product of zero leaves the sum as it is)
+            float w8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w8[j] = j < r ? qs_sh[j] : 0.0f;
+            const int t_last4 = (t_end - 1) & ~3;
+            for (int t0 = t_begin + tid * 4; t0 < t_end; t0 += kWG * 16) {
+                uint4 cv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    cv[i] = *reinterpret_cast<const uint4 *>(cu + min(t0 + i * kWG * 4, t_last4));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int t = t0 + i * kWG * 4 + e;
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(w8[j], nib(c4[e], j), acc);
+                        if (t < t_end) {
+                            const uint32_t key = score_key(acc);
+                            st_dev(ku + t, key);
+                            atomicAdd(&lh[key >> kKeyShift], 1u);
+                        }
+                    }
+                }
+            }
+        } else {
+            for (int t = t_begin + tid; t < t_end; t += kWG) {
+                float acc = 0.0f;
+                for (int w = 0; w < W; ++w) {
+                    const uint32_t word = cu[(size_t)t * W + w];
+                    for (int i = 0; i < 8 && w * 8 + i < r; ++i)
+                        acc = __builtin_fmaf(qs_sh[w * 8 + i], nib(word, i), acc);
+                }
+                const uint32_t key = score_key(acc);
+                st_dev(ku + t, key);
+                atomicAdd(&lh[key >> kKeyShift], 1u);
+            }
         }
     } else if constexpr (RMODE == -2) {
         const _Float16 *Ku = label + (size_t)u * L_max * kD;
@@ -544,7 +595,7 @@ hipError_t launch_init(void *ws, size_t bytes, hipStream_t st)
 
 hipError_t launch_score(const void *q, const void *label, const int32_t *channels, void *ws,
                         const Plan &p, const ds_shape_t &s, bool tail_refine, bool want_offsets,
-                        hipStream_t st, bool label_is_k)
+                        hipStream_t st, ScoreSrc src)
 {
     const dim3 grid(p.n_sc, p.units), block(kWG);
     auto *keys = reinterpret_cast<uint32_t *>(wsp(ws, p.off_keys));
@@ -555,10 +606,11 @@ hipError_t launch_score(const void *q, const void *label, const int32_t *channel
     const auto *qh = static_cast<const _Float16 *>(q);
     const auto *lh = static_cast<const _Float16 *>(label);
 #define DS_SCORE(MODE)                                                                            \
-    DS_LAUNCH(KID_SCORE, k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, keys, hist,     \
+    DS_LAUNCH(KID_SCORE, k_score<MODE>, grid, block, (size_t)p.n_ch * 4, st, qh, lh, channels, src.amax, keys, hist, \
                        coarse, ctl, offs, s.Hq, s.Hkv, p.G, s.L, s.L_max, s.r, p.key_stride, p.sc_chunk,       \
                        p.k_eff, tail_refine ? 1 : 0, want_offsets ? 1 : 0, p.ch, p.n_ch)
-    if (label_is_k) DS_SCORE(-2);
+    if (src.kind == SRC_Q4) DS_SCORE(-3);
+    else if (src.kind == SRC_K_ROWS) DS_SCORE(-2);
     else if (s.r == 8) DS_SCORE(8);
     else if (s.r == 16) DS_SCORE(16);
     else if (s.r % 8 == 0) DS_SCORE(0);

@@ -8,7 +8,7 @@ import torch
 
 import paper_2408_07092_amd as ds
 from oracle import ds_oracle as O
-from tests.parity_util import Case, check_index_structure, check_output, full_parity, to_dev
+from tests.parity_util import Case, check_index_band, check_index_structure, check_output, full_parity, to_dev
 from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_numpy, make_layer_torch,
                        outlier_channels)
 
@@ -393,6 +393,92 @@ def test_interleaved_cache_append_and_decode(B, Hq, Hkv, L, L_max, r, k):
     with pytest.raises(ds.DsError) as e:
         ds.ds_append_kv(to_dev(K[:, :, :2]), to_dev(V[:, :, :2]), K_d, None, ch_d, lab_d, shp, 0, 2, ds.DS_KV_SPLIT)
     assert e.value.status == ds.DS_ERR_NULL
+
+
+# ---------------------------------------------------------------- 4-bit label cache
+def _q4_parity(q, K, V, ch, L, k, what, split=None):
+    """Codes and amax bit-exact against the oracle's quantiser; selection identical to the
+    oracle scoring the same codes in binary32 order, inside the near-tie band of its
+    float64 scores; output to the usual bar."""
+    B, Hq, _ = q.shape
+    _, Hkv, L_max, _ = K.shape
+    r = ch.shape[1]
+    W = (r + 7) // 8
+    shp = ds.shape(B, Hq, Hkv, 128, L, L_max, r, k)
+    K_d, V_d, q_d, ch_d = to_dev(K), to_dev(V), to_dev(q), to_dev(ch)
+    codes = torch.zeros((B, Hkv, L_max, W), dtype=torch.int32, device="cuda")
+    amax = torch.full((B, Hkv, r), -1.0, dtype=torch.float32, device="cuda")
+    codes_ref, amax_ref = O.build_label_q4(K, ch, L)
+    if split is None:
+        ds.ds_build_label_q4(K_d, ch_d, codes, amax, shp)
+    else:   # prefill `split` tokens' worth of amax over all L, then code in two pieces
+        ds.ds_build_label_q4(K_d, ch_d, codes, amax, shp)
+        codes.zero_()
+        ds.ds_append_label_q4(K_d, ch_d, codes, amax, shp, 0, split)
+        ds.ds_append_label_q4(K_d, ch_d, codes, amax, shp, split, L - split)
+    torch.cuda.synchronize()
+    assert np.array_equal(amax.cpu().numpy(), amax_ref), f"{what}: amax differs"
+    assert np.array_equal(codes.cpu().numpy().view(np.uint32), codes_ref), f"{what}: 4-bit codes differ"
+    ws = ds.ds_workspace_alloc(shp)
+    out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda")
+    ds.ds_sparse_decode_q4(q_d, codes, amax, K_d, V_d, ch_d, out, idx, ws, shp)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    check_index_structure(idx_h, L, k)
+    out32, idx32 = O.sparse_decode_q4(q, codes_ref, amax_ref, K, V, ch, L, k, precision=32)
+    assert np.array_equal(idx_h, idx32), f"{what}: index sets differ from the binary32-order oracle"
+    out64, idx64, sc64, srt64 = O.sparse_decode_q4(q, codes_ref, amax_ref, K, V, ch, L, k, want_scores=True)
+    differing = check_index_band(idx_h, sc64, srt64, L, k)
+    ref = out64 if differing == 0 else O.attend_idx(q, K, V, idx_h)
+    rep = check_output(out.cpu().numpy(), ref, what)
+    out2 = torch.empty_like(out)
+    ds.ds_sparse_decode_q4(q_d, codes, amax, K_d, V_d, ch_d, out2, None, ws, shp)
+    torch.cuda.synchronize()
+    assert out2.cpu().numpy().tobytes() == out.cpu().numpy().tobytes()
+    return rep
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", [
+    (1, 1, 1, 1, 1, 8, 1),
+    (2, 4, 4, 63, 64, 8, 7),
+    (1, 3, 3, 257, 300, 16, 16),      # L_max not a multiple of 4: per-token loads
+    (2, 2, 2, 1000, 1000, 8, 62),
+    (1, 4, 4, 4097, 4100, 8, 256),
+    (1, 2, 2, 1500, 1500, 3, 100),    # r < 8: zero nibbles
+    (1, 2, 2, 1500, 1500, 11, 100),   # two words per token, second partly used
+    (3, 8, 2, 900, 1024, 8, 57),      # GQA group 4
+    (1, 2, 2, 9000, 9000, 8, 600),    # refine-and-attend launch
+])
+def test_q4_label_cache_small_shapes(B, Hq, Hkv, L, L_max, r, k):
+    w = small_workload(B, Hq, Hkv, L, r, k)
+    t = make_layer_numpy(w, L_max=L_max)
+    _q4_parity(t["q"], t["K"], t["V"], rand_channels(Hkv, 128, r, seed=L + r), L, k, "q4 small",
+               split=None if L < 10 else L // 3)
+
+
+def test_q4_label_cache_zero_channel_and_ties():
+    """A label channel that is zero everywhere (amax = 0) and small-integer keys (many ties)."""
+    rng = np.random.default_rng(5)
+    L, k = 2000, 150
+    q = rng.integers(-2, 3, size=(1, 2, 128)).astype(np.float16)
+    K = rng.integers(-2, 3, size=(1, 2, L, 128)).astype(np.float16)
+    V = rng.standard_normal((1, 2, L, 128)).astype(np.float16)
+    ch = rand_channels(2, 128, 8, seed=2)
+    K[0, 0, :, ch[0, 3]] = 0
+    _q4_parity(q, K, V, ch, L, k, "q4 ties")
+
+
+@pytest.mark.parametrize("name", ["C1", "C3", "C2"])
+def test_q4_label_cache_full_config(name):
+    w = WORKLOADS[name]
+    qc, kc = make_calibration_numpy(w)
+    ch = ds.ds_calibrate_channels(qc, kc, w.r, ds.DS_CALIB_QK)
+    t = make_layer_torch(w, "cuda", layer=0)
+    q, K, V = (t[x].cpu().numpy() for x in ("q", "K", "V"))
+    del t
+    torch.cuda.empty_cache()
+    print(name, "q4", _q4_parity(q, K, V, ch, w.L, w.k, name + " q4"))
 
 
 # ---------------------------------------------------------------- determinism across tuning-independent reruns

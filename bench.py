@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--tune", default="", help="knob=value,... (ds_tune_set)")
     ap.add_argument("--interleaved", action="store_true",
                     help="K|V cache as one [L,2,d] array per head (512-byte gathers), ds_sparse_decode_kv")
+    ap.add_argument("--label-bits", type=int, default=16, choices=(16, 4),
+                    help="label cache precision: fp16 (the metric's configuration) or the 4-bit cache")
     ap.add_argument("--label-ablation", action="store_true",
                     help="with / without label cache over the batch x length grid of the paper's ablation table")
     return ap.parse_args()
@@ -97,6 +99,11 @@ def main():
         t = make_layer_torch(w, dev, layer=l)
         label = torch.empty((w.B, w.Hkv, w.L, w.r), dtype=torch.float16, device=dev)
         ds.ds_build_label(t["K"], ch, label, shp)
+        if args.label_bits == 4:
+            codes = torch.empty((w.B, w.Hkv, w.L, (w.r + 7) // 8), dtype=torch.int32, device=dev)
+            amax = torch.empty((w.B, w.Hkv, w.r), dtype=torch.float32, device=dev)
+            ds.ds_build_label_q4(t["K"], ch, codes, amax, shp)
+            label = (codes, amax)
         if args.interleaved:
             KV = torch.stack((t["K"], t["V"]), dim=3).contiguous()
             layers.append((t["q"], label, KV, None, ch))
@@ -113,6 +120,8 @@ def main():
         for (q, label, K, V, ch) in layers:
             if V is None:
                 ds.ds_sparse_decode_kv(q, label, K, ch, out, None, ws, shp)
+            elif args.label_bits == 4:
+                ds.ds_sparse_decode_q4(q, label[0], label[1], K, V, ch, out, None, ws, shp)
             else:
                 ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
 
@@ -196,13 +205,16 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.note}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "L": w.L,
                    "r": w.r, "k": w.k, "storage": "f16", "layers_per_step": n_layers, "hip_graph": use_graph,
-                   "kv_layout": "interleaved [L,2,d]" if args.interleaved else "separate K, V [L,d]"},
+                   "kv_layout": "interleaved [L,2,d]" if args.interleaved else "separate K, V [L,d]",
+                   "label_bits": args.label_bits},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None if args.interleaved else counted_traffic(w.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
     }
     alg = w.algorithmic_bytes()
+    if args.label_bits == 4:   # 4 bits per label value, eight to a word
+        alg = w.units * (w.L * ((w.r + 7) // 8) * 4 + w.k * w.d * 2 * 2)
     extra = {
         "algorithmic_bytes_per_layer": alg,
         "achieved_GBps_whole_path": round(alg / (us_layer * 1e-6) / 1e9, 1),
@@ -224,7 +236,7 @@ def main():
         extra["speedup_vs_dense"] = round(d_us / us_layer, 3)
 
     # ---- the same decode scoring straight from the K rows (what the label cache buys; Sec. 4.2)
-    if not args.no_dense and not args.interleaved:
+    if not args.no_dense and not args.interleaved and args.label_bits == 16:
         n_ms, _ = timed(nolabel_sweep, max(2, args.steps // 4), 1, use_graph)
         extra["nolabel_us_per_layer"] = round(n_ms * 1e3 / n_layers, 3)
         extra["label_cache_speedup"] = round(n_ms * 1e3 / n_layers / us_layer, 3)
@@ -237,8 +249,8 @@ def main():
             ds.ds_probe_stream_read(K, sink)
     p_ms, _ = timed(probe_sweep, max(2, args.steps // 4), 1, use_graph)
     extra["stream_read_ceiling_GBps"] = round(n_layers * layers[0][2].numel() * 2 / (p_ms * 1e-3) / 1e9, 1)
-    if args.interleaved:
-        args.no_cpu = True   # the oracle sample below reads the separate layout
+    if args.interleaved or args.label_bits == 4:
+        args.no_cpu = True   # the oracle sample below is the fp16-label, separate-layout path
 
     # ---- CPU oracle on the host cores, bounded sample
     if not args.no_cpu:

@@ -14,6 +14,8 @@
 //   k_compact writes that index list (for callers that only want indices).
 // All counters are integers, so the result does not depend on the order in
 // which workgroups or atomics complete.
+#include <type_traits>
+
 #include "ds_device.h"
 
 namespace ds {
@@ -76,6 +78,11 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     const int t_end = min(L, t_begin + sc_chunk);
     const _Float16 *lab = label + (size_t)u * L_max * r;
     uint32_t *ku = keys + (size_t)u * key_stride;
+    // keys are written through only when this launch's own tail reads them back
+    auto put_key = [&](uint32_t *p, uint32_t key) {
+        if (tail_refine) st_dev(p, key);
+        else *p = key;
+    };
 
     // Fast modes: eight tokens per thread per pass, every load of a pass issued before the
     // first use; lanes past the end re-read the chunk's last token (in bounds) and drop the
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                 const int t = t0 + i * kWG;
                 if (t < t_end) {
                     const uint32_t key = score_key(acc);
-                    st_dev(ku + t, key);  // written through: the unit's last workgroup may read it
+                    put_key(ku + t, key);
                     atomicAdd(&lh[key >> kKeyShift], 1u);
                 }
             }
@@ -153,35 +160,45 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
         const int W = (r + 7) / 8;
         const uint32_t *cu = reinterpret_cast<const uint32_t *>(label) + (size_t)u * L_max * W;
         auto nib = [](uint32_t word, int i) { return (float)(((int32_t)(word << (28 - 4 * i))) >> 28); };
-        if (W == 1 && (L_max & 3) == 0) {
-            // four tokens per 16-byte load, four loads in flight; r <= 8 with w[j] = 0 beyond r
-            // (a product of zero leaves the sum as it is)
-            float w8[8];
+        // One or two words per token: 16-byte loads of four or two tokens, four loads in flight;
+        // w[j] = 0 beyond r (a product of zero leaves the sum as it is).
+        auto run_packed = [&](auto wc) {
+            constexpr int WW = decltype(wc)::value;  // words per token
+            constexpr int TPL = 4 / WW;              // tokens per 16-byte load
+            float wr[8 * WW];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) w8[j] = j < r ? qs_sh[j] : 0.0f;
-            const int t_last4 = (t_end - 1) & ~3;
-            for (int t0 = t_begin + tid * 4; t0 < t_end; t0 += kWG * 16) {
+            for (int j = 0; j < 8 * WW; ++j) wr[j] = j < r ? qs_sh[j] : 0.0f;
+            const int t_lastq = (t_end - 1) & ~(TPL - 1);
+            for (int t0 = t_begin + tid * TPL; t0 < t_end; t0 += kWG * TPL * 4) {
                 uint4 cv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    cv[i] = *reinterpret_cast<const uint4 *>(cu + min(t0 + i * kWG * 4, t_last4));
+                    cv[i] = *reinterpret_cast<const uint4 *>(cu + (size_t)min(t0 + i * kWG * TPL, t_lastq) * WW);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int t = t0 + i * kWG * 4 + e;
+                    for (int e = 0; e < TPL; ++e) {
+                        const int t = t0 + i * kWG * TPL + e;
                         float acc = 0.0f;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(w8[j], nib(c4[e], j), acc);
+                        for (int w = 0; w < WW; ++w)
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                acc = __builtin_fmaf(wr[w * 8 + j], nib(c4[e * WW + w], j), acc);
                         if (t < t_end) {
                             const uint32_t key = score_key(acc);
-                            st_dev(ku + t, key);
+                            put_key(ku + t, key);
                             atomicAdd(&lh[key >> kKeyShift], 1u);
                         }
                     }
                 }
             }
+        };
+        if (W == 1 && (L_max & 3) == 0) {
+            run_packed(std::integral_constant<int, 1>{});
+        } else if (W == 2 && (L_max & 1) == 0) {
+            run_packed(std::integral_constant<int, 2>{});
         } else {
             for (int t = t_begin + tid; t < t_end; t += kWG) {
                 float acc = 0.0f;
@@ -191,7 +208,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                         acc = __builtin_fmaf(qs_sh[w * 8 + i], nib(word, i), acc);
                 }
                 const uint32_t key = score_key(acc);
-                st_dev(ku + t, key);
+                put_key(ku + t, key);
                 atomicAdd(&lh[key >> kKeyShift], 1u);
             }
         }
@@ -214,7 +231,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                 const int t = t0 + i * kWG;
                 if (t < t_end) {
                     const uint32_t key = score_key(acc[i]);
-                    st_dev(ku + t, key);
+                    put_key(ku + t, key);
                     atomicAdd(&lh[key >> kKeyShift], 1u);
                 }
             }
@@ -222,7 +239,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     } else {
         for (int t = t_begin + tid; t < t_end; t += kWG) {
             const uint32_t key = score_key(label_dot<RMODE>(lab + (size_t)t * r, qs_sh, r));
-            st_dev(ku + t, key);
+            put_key(ku + t, key);
             atomicAdd(&lh[key >> kKeyShift], 1u);
         }
     }

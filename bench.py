@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--tune", default="", help="knob=value,... (ds_tune_set)")
     ap.add_argument("--interleaved", action="store_true",
                     help="K|V cache as one [L,2,d] array per head (512-byte gathers), ds_sparse_decode_kv")
+    ap.add_argument("--predict", action="store_true",
+                    help="C5: select with queries predicted from the previous layer's embedding (W_q GEMV on the select stream)")
     ap.add_argument("--label-bits", type=int, default=16, choices=(16, 4),
                     help="label cache precision: fp16 (the metric's configuration) or the 4-bit cache")
     ap.add_argument("--label-ablation", action="store_true",
@@ -358,17 +360,50 @@ def bench_offload(args, w, ds, torch, dev):
         del Kd
         layers.append((t["q"], label, ch, t["K"], t["V"]))
         outs.append(torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev))
+    predict = None
+    if args.predict:
+        # synthetic stand-ins of the model around the attention: one embedding per layer and the
+        # layer's query projection (7B shape: Dm = Hq * d), random; only the shape of the work matters
+        Dm = w.Hq * w.d
+        g = torch.Generator(device=dev); g.manual_seed(7)
+        predict = []
+        for l in range(n_layers):
+            x = torch.randn((w.B, Dm), generator=g, device=dev, dtype=torch.float32).to(torch.float16)
+            Wq = (torch.randn((w.Hq * w.d, Dm), generator=g, device=dev, dtype=torch.float32) / Dm ** 0.5).to(torch.float16)
+            predict.append((x, Wq, torch.empty((w.B, w.Hq, w.d), dtype=torch.float16, device=dev)))
     dec = OffloadDecoder(shp, dev)
     torch.cuda.synchronize()
     for _ in range(args.warmup):
-        dec.decode(layers, outs)
+        dec.decode(layers, outs, predict)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        dec.decode(layers, outs)
+        dec.decode(layers, outs, predict)
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
     us_layer = ms_step * 1e3 / n_layers
+    # the same stages one after the other on one stream: what the schedule hides
+    stage = {"predict": 0.0, "select": 0.0, "fetch": 0.0, "attend": 0.0}
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    for l in range(n_layers):
+        q, label, ch, Kp, Vp = layers[l]
+        ev[0].record()
+        if predict is not None:
+            ds.ds_predict_query(*predict[l]); q_sel = predict[l][2]
+        else:
+            q_sel = q
+        ev[1].record()
+        ds.ds_select(q_sel, label, ch, dec.idx[0], dec.ws_sel[0], shp)
+        ev[2].record()
+        ds.ds_gather_rows_host(Kp, Vp, dec.idx[0], dec.rows[0], shp)
+        ev[3].record()
+        ds.ds_attend_rows(q, dec.rows[0], outs[l], dec.ws_att, shp)
+        ev[4].record()
+        torch.cuda.synchronize()
+        for i, name in enumerate(("predict", "select", "fetch", "attend")):
+            stage[name] += ev[i].elapsed_time(ev[i + 1]) * 1e3 / n_layers
+    serial = sum(stage.values())
+    hidden = (serial - us_layer) / max(serial - max(stage.values()), 1e-9)
     link_bytes = w.units * w.k * w.d * 2 * 2
     # measured host-to-device ceiling: one large pinned -> device copy
     big = layers[0][3].view(-1)[: (1 << 29)]
@@ -390,7 +425,11 @@ def bench_offload(args, w, ds, torch, dev):
         "roofline": {"bound": "host-link", "kernel": "k_gather_host", "achieved": round(link, 1), "peak": round(h2d, 1),
                      "unit": "GB/s", "frac": round(link / h2d, 4), "traffic": None,
                      "note": "peak = measured pinned->device copy rate of this box, not a published figure"},
-        "extra": {"link_bytes_per_layer": link_bytes, "hbm_label_bytes_per_layer": w.units * w.L * w.r * 2},
+        "extra": {"link_bytes_per_layer": link_bytes, "hbm_label_bytes_per_layer": w.units * w.L * w.r * 2,
+                  "query_prediction": bool(args.predict),
+                  "stage_us_per_layer_serial": {k_: round(v, 2) for k_, v in stage.items()},
+                  "serial_us_per_layer": round(serial, 2),
+                  "overlap_fraction": round(hidden, 4)},
     }
     print(json.dumps(res))
 

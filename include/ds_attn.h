@@ -230,6 +230,21 @@ ds_status_t ds_dense_decode(const void *q, const void *K, const void *V, float *
                             const ds_shape_t *shape, void *stream);
 
 /*
+ * Query prediction of the offload schedule (Sec. 5.1): a layer's input
+ * embedding is passed through the NEXT layer's query projection to get an
+ * approximate query for that layer, whose selected rows can then be fetched
+ * while the current layer still computes.
+ *   q_out[b, n] = sum_m Wq[n, m] * x[b, m]
+ * x [B, Dm] fp16, Wq [N, Dm] fp16 (row n = output feature n; N = Hq * d gives
+ * q_out the [B, Hq, d] layout of the decode calls), q_out [B, N] fp16.  DEVICE
+ * pointers; x and Wq 16-byte aligned; Dm a multiple of 8, at most 8192.
+ * Products are exact, sums are binary32 in a fixed order, one rounding to fp16.
+ * (Positional encoding and normalisation belong to the model around this call.)
+ */
+ds_status_t ds_predict_query(const void *x, const void *Wq, void *q_out, int32_t B,
+                             int32_t Dm, int32_t N, void *stream);
+
+/*
  * Split entry points for the offload arrangement (Sec. 5.1: label cache on the
  * GPU, full K/V in host memory, only the selected rows fetched).
  * ds_select      = steps 1-2 of Algorithm 1; idx_out (required) as above.

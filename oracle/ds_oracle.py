@@ -87,6 +87,14 @@ def append_kv(k_new, v_new, K, V, channels, label, t0):
     return label_write(K, channels, label, t0, n)
 
 
+def predict_query(x, Wq):
+    """Sec. 5.1: the approximate query of the next layer, its query projection applied
+    to this layer's input embedding: q[b, n] = sum_m Wq[n, m] x[b, m], in float64,
+    rounded once to fp16.  x [B, Dm], Wq [N, Dm] fp16 -> [B, N] fp16."""
+    x = _u16(x, "x"); Wq = _u16(Wq, "Wq")
+    return (x.astype(np.float64) @ Wq.astype(np.float64).T).astype(np.float16)
+
+
 def interleave_kv(K, V):
     """[B,Hkv,L_max,2,d]: each token's K row followed by its V row."""
     return np.ascontiguousarray(np.stack([K, V], axis=3))

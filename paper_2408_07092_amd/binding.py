@@ -25,7 +25,7 @@ EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
     "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_sparse_decode_nolabel",
     "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_build_label_q4",
-    "ds_append_label_q4", "ds_sparse_decode_q4", "ds_dense_decode", "ds_select",
+    "ds_append_label_q4", "ds_sparse_decode_q4", "ds_predict_query", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
     "ds_tune_set", "ds_tune_get",
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.ds_sparse_decode_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, shp, i32, i32, ctypes.c_int, vp]
         L.ds_build_label_kv.argtypes = [vp, vp, vp, shp, vp]
+        L.ds_predict_query.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         L.ds_build_label_q4.argtypes = [vp, vp, vp, vp, shp, vp]
         L.ds_append_label_q4.argtypes = [vp, vp, vp, vp, shp, i32, i32, vp]
         L.ds_sparse_decode_q4.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
@@ -214,6 +215,14 @@ def ds_sparse_decode_q4(q, label_q4, amax, K, V, channels, out, idx_out, workspa
                                      _dp(out), _dp(idx_out), _dp(workspace),
                                      workspace.numel() * workspace.element_size(),
                                      ctypes.byref(shp), _stream(stream)), "ds_sparse_decode_q4")
+
+
+def ds_predict_query(x, Wq, q_out, stream=None):
+    """x [B, Dm], Wq [N, Dm], q_out [B, ...] with N elements per batch row (all fp16)."""
+    B, Dm = x.shape
+    N = Wq.shape[0]
+    assert Wq.shape[1] == Dm and q_out.numel() == B * N
+    _check(lib().ds_predict_query(_dp(x), _dp(Wq), _dp(q_out), B, Dm, N, _stream(stream)), "ds_predict_query")
 
 
 def ds_dense_decode(q, K, V, out, workspace, shp: DsShape, stream=None):

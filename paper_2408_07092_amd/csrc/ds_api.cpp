@@ -115,7 +115,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
     "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2",
-    "k_refine_attend", "k_append_kv", "k_q4_amax", "k_q4_write"};
+    "k_refine_attend", "k_append_kv", "k_q4_amax", "k_q4_write", "k_predict_query"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
@@ -462,6 +462,17 @@ ds_status_t ds_dense_decode(const void *q, const void *K, const void *V, float *
     if (workspace_bytes < p.total) return DS_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     DS_TRY(launch_attend_dense(q, K, V, workspace, out, p, *shape, st));
+    return DS_OK;
+}
+
+ds_status_t ds_predict_query(const void *x, const void *Wq, void *q_out, int32_t B, int32_t Dm,
+                             int32_t N, void *stream)
+{
+    if (!x || !Wq || !q_out) return DS_ERR_NULL;
+    // 16-byte pieces of a row; x for up to four batch rows has to fit the 64 KiB of LDS asked for
+    if (B < 1 || N < 1 || Dm < 8 || Dm % 8 != 0 || Dm > 8192) return DS_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(Wq, 16) || !aligned(q_out, 2)) return DS_ERR_ALIGN;
+    DS_TRY(launch_predict_query(x, Wq, q_out, B, Dm, N, (hipStream_t)stream));
     return DS_OK;
 }
 

@@ -56,6 +56,7 @@ enum KernelId {
     KID_APPEND_KV,
     KID_Q4_AMAX,
     KID_Q4_WRITE,
+    KID_PREDICT,
     KID_COUNT
 };
 
@@ -127,6 +128,8 @@ hipError_t launch_q4_amax(const void *K, const int32_t *channels, float *amax, c
                           hipStream_t st);
 hipError_t launch_q4_write(const void *K, const int32_t *channels, const float *amax, void *codes,
                            const ds_shape_t &s, int t0, int n, hipStream_t st);
+hipError_t launch_predict_query(const void *x, const void *Wq, void *q_out, int B, int Dm, int N,
+                                hipStream_t st);
 hipError_t launch_append_kv(const void *k_new, const void *v_new, void *K, void *V,
                             const int32_t *channels, void *label, const ds_shape_t &s, int t0, int n,
                             int kv_stride, hipStream_t st);

@@ -127,6 +127,57 @@ __global__ __launch_bounds__(kWG) void k_q4_write(const _Float16 *__restrict__ K
     }
 }
 
+// ---------------------------------------------------------------- next-layer query prediction (Sec. 5.1)
+// q_out[b, n] = sum_m Wq[n, m] * x[b, m], the shape of the step that turns a layer's input
+// embedding into an approximate query of the NEXT layer so that its rows can be fetched early.
+// Bound by the one read of Wq.  A wavefront owns an output feature n at a time: its 64 lanes
+// split m in 16-byte pieces, products are exact (fp16 x fp16) and accumulated in binary32, the
+// lanes are summed in a fixed butterfly, the result is rounded once to fp16.  Up to four batch
+// rows share a pass over Wq (x sits in LDS); larger batches take several passes.
+constexpr int kPredBatch = 4;
+
+__global__ __launch_bounds__(kWG) void k_predict_query(const _Float16 *__restrict__ x,
+                                                       const _Float16 *__restrict__ Wq,
+                                                       _Float16 *__restrict__ q_out, int B, int Dm,
+                                                       int N, int rows_per_wg)
+{
+    extern __shared__ __attribute__((aligned(16))) _Float16 x_sh[];  // [min(B, kPredBatch)][Dm]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_lo = blockIdx.x * rows_per_wg, n_hi = min(N, n_lo + rows_per_wg);
+    for (int b0 = 0; b0 < B; b0 += kPredBatch) {
+        const int nb = min(kPredBatch, B - b0);
+        __syncthreads();
+        for (int i = tid * 8; i < nb * Dm; i += kWG * 8)
+            *reinterpret_cast<uint4 *>(x_sh + i) = *reinterpret_cast<const uint4 *>(x + (size_t)b0 * Dm + i);
+        __syncthreads();
+        for (int n = n_lo + wave; n < n_hi; n += 4) {
+            const _Float16 *wrow = Wq + (size_t)n * Dm;
+            float acc[kPredBatch] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int m = lane * 8; m < Dm; m += 64 * 8) {
+                const half8 wv = *reinterpret_cast<const half8 *>(wrow + m);
+#pragma unroll
+                for (int b = 0; b < kPredBatch; ++b) {
+                    if (b < nb) {
+                        const half8 xv = *reinterpret_cast<const half8 *>(x_sh + b * Dm + m);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const half2v a2 = {wv[2 * e], wv[2 * e + 1]};
+                            const half2v b2 = {xv[2 * e], xv[2 * e + 1]};
+                            acc[b] = __builtin_amdgcn_fdot2(a2, b2, acc[b], false);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kPredBatch; ++b) {
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) acc[b] += __shfl_xor(acc[b], o);
+                if (lane == 0 && b < nb) q_out[(size_t)(b0 + b) * N + n] = (_Float16)acc[b];
+            }
+        }
+    }
+}
+
 // rows[u, i, 0, :] = K_host[u, idx[u, i], :], rows[u, i, 1, :] = V_host[...]:
 // 16 lanes move one 256-byte row; K_host / V_host are pinned host memory read
 // over the host link by the kernel itself.
@@ -207,6 +258,20 @@ hipError_t launch_q4_write(const void *K, const int32_t *channels, const float *
     DS_LAUNCH(KID_Q4_WRITE, k_q4_write, dim3((unsigned)blocks, s.B * s.Hkv), dim3(kWG), 0, st,
               static_cast<const _Float16 *>(K), channels, amax, static_cast<uint32_t *>(codes), s.Hkv,
               s.L_max, s.r, t0, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_predict_query(const void *x, const void *Wq, void *q_out, int B, int Dm, int N,
+                                hipStream_t st)
+{
+    // about two workgroups per CU; every workgroup re-reads x once per batch pass
+    int rows_per_wg = (N + 511) / 512;
+    rows_per_wg = (rows_per_wg + 3) & ~3;
+    const int blocks = (N + rows_per_wg - 1) / rows_per_wg;
+    const size_t shmem = (size_t)std::min(B, kPredBatch) * Dm * sizeof(_Float16);
+    DS_LAUNCH(KID_PREDICT, k_predict_query, dim3((unsigned)blocks), dim3(kWG), shmem, st,
+              static_cast<const _Float16 *>(x), static_cast<const _Float16 *>(Wq),
+              static_cast<_Float16 *>(q_out), B, Dm, N, rows_per_wg);
     return hipGetLastError();
 }
 

@@ -8,9 +8,12 @@ in the library's kernels:
     select stream : ds_select(l)            -> idx[l % 2]
     copy stream   : ds_gather_rows_host(l)  -> rows[l % 2]   (reads pinned host memory)
     main stream   : ds_attend_rows(l)       -> out[l]
-Row fetch of layer l+1 overlaps the attention of layer l.  (The paper obtains
-layer l+1's query early by pushing layer l's embedding through W_q of layer l+1;
-here the queries are given, which exercises the same transport.)
+Row fetch of layer l+1 overlaps the attention of layer l.  The paper obtains
+layer l+1's query early by pushing layer l's embedding through W_q of layer l+1
+(Sec. 5.1); with `predict` the select stream does exactly that
+(ds_predict_query) and selects with the approximate query, while the attention
+uses the layer's real query.  Without it the given queries select, which
+exercises the same transport.
 """
 from __future__ import annotations
 
@@ -35,9 +38,12 @@ class OffloadDecoder:
         self.ev_rows = [torch.cuda.Event() for _ in range(2)]
         self.ev_free = [torch.cuda.Event() for _ in range(2)]
 
-    def decode(self, layers, outs):
+    def decode(self, layers, outs, predict=None):
         """layers: list of (q, label, channels, K_pinned, V_pinned); outs: list of
-        [B,Hq,d] fp32 device tensors.  Enqueues one decode step over all layers on the
+        [B,Hq,d] fp32 device tensors.  predict: None, or per layer (x, Wq, q_pred) with
+        x [B,Dm] the embedding the prediction starts from, Wq [Hq*d, Dm] the layer's
+        query projection and q_pred [B,Hq,d] fp16 receiving the approximate query that
+        then selects the layer's rows.  Enqueues one decode step over all layers on the
         current stream (plus the two helper streams) and returns without synchronising."""
         main = torch.cuda.current_stream(self.dev)
         start = torch.cuda.Event()
@@ -52,6 +58,10 @@ class OffloadDecoder:
             if l >= 2:
                 self.s_sel.wait_event(self.ev_free[s])     # attention of layer l-2 released the buffers
             with torch.cuda.stream(self.s_sel):
+                if predict is not None:
+                    x, Wq, q_pred = predict[l]
+                    ds.ds_predict_query(x, Wq, q_pred)
+                    q = q_pred
                 ds.ds_select(q, label, ch, self.idx[s], self.ws_sel[s], self.shp)
                 self.ev_sel[s].record(self.s_sel)
             with torch.cuda.stream(self.s_copy):

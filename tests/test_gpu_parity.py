@@ -395,6 +395,79 @@ def test_interleaved_cache_append_and_decode(B, Hq, Hkv, L, L_max, r, k):
     assert e.value.status == ds.DS_ERR_NULL
 
 
+# ---------------------------------------------------------------- query prediction + offload schedule
+@pytest.mark.parametrize("B,Dm,N", [(1, 8, 1), (1, 4096, 4096), (3, 520, 77), (4, 1024, 256), (9, 2048, 128),
+                                    (2, 8192, 64)])
+def test_predict_query_matches_oracle(B, Dm, N):
+    """fp32 accumulation against the float64 oracle, both rounded once to fp16: equal up to
+    one fp16 step of the result plus the binary32 accumulation error of the Dm products."""
+    rng = np.random.default_rng(Dm + N)
+    x = rng.standard_normal((B, Dm)).astype(np.float16)
+    Wq = (rng.standard_normal((N, Dm)) / np.sqrt(Dm)).astype(np.float16)
+    q = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    ds.ds_predict_query(to_dev(x), to_dev(Wq), q)
+    torch.cuda.synchronize()
+    got = q.cpu().numpy().astype(np.float64)
+    ref = O.predict_query(x, Wq).astype(np.float64)
+    mag = np.abs(x.astype(np.float64)) @ np.abs(Wq.astype(np.float64)).T
+    tol = 2.0 ** -10 * np.abs(ref) + Dm * 2.0 ** -24 * mag + 2.0 ** -24
+    assert np.isfinite(got).all() and (np.abs(got - ref) <= tol).all()
+    q2 = torch.empty_like(q)
+    ds.ds_predict_query(to_dev(x), to_dev(Wq), q2)
+    torch.cuda.synchronize()
+    assert q2.cpu().numpy().tobytes() == q.cpu().numpy().tobytes()
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_predict_query(to_dev(x[:, :Dm - 1].copy()) if Dm > 8 else to_dev(x[:, :4].copy()),
+                            to_dev(Wq[:, :Dm - 1].copy()) if Dm > 8 else to_dev(Wq[:, :4].copy()), q)
+    assert e.value.status == ds.DS_ERR_SHAPE
+
+
+def test_offload_schedule_with_predicted_queries_matches_oracle_over_layers():
+    """Sec. 5.1 schedule: layer l's rows are selected with the query predicted from the
+    previous layer's embedding (W_q of layer l applied to it), fetched from pinned host
+    memory into the double buffer, and attended with the layer's real query."""
+    from paper_2408_07092_amd.offload import OffloadDecoder
+    B, Hq, Hkv, L, r, k, n_layers, Dm = 2, 4, 4, 3000, 8, 200, 5, 512
+    w = small_workload(B, Hq, Hkv, L, r, k)
+    shp = ds.shape(B, Hq, Hkv, 128, L, L, r, k)
+    rng = np.random.default_rng(11)
+    layers, outs, predict, host = [], [], [], []
+    x_prev = rng.standard_normal((B, Dm)).astype(np.float16)
+    for l in range(n_layers):
+        t = make_layer_numpy(w, layer=l)
+        ch = rand_channels(Hkv, 128, r, seed=l)
+        Wq = (rng.standard_normal((Hq * 128, Dm)) / np.sqrt(Dm) * 4).astype(np.float16)
+        Kp = torch.from_numpy(t["K"]).pin_memory()
+        Vp = torch.from_numpy(t["V"]).pin_memory()
+        label = torch.empty((B, Hkv, L, r), dtype=torch.float16, device="cuda")
+        Kd = to_dev(t["K"])
+        ds.ds_build_label(Kd, to_dev(ch), label, shp)
+        torch.cuda.synchronize()
+        del Kd
+        q_pred = torch.zeros((B, Hq, 128), dtype=torch.float16, device="cuda")
+        layers.append((to_dev(t["q"]), label, to_dev(ch), Kp, Vp))
+        predict.append((to_dev(x_prev), to_dev(Wq), q_pred))
+        outs.append(torch.full((B, Hq, 128), float("nan"), dtype=torch.float32, device="cuda"))
+        host.append((t, ch, Wq, x_prev))
+        x_prev = (x_prev.astype(np.float32) * 0.9 + 0.1 * rng.standard_normal((B, Dm))).astype(np.float16)
+    dec = OffloadDecoder(shp)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        dec.decode(layers, outs, predict)
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            t, ch, Wq, x = host[l]
+            qp = predict[l][2].cpu().numpy()
+            ref_q = O.predict_query(x, Wq).reshape(B, Hq, 128).astype(np.float64)
+            assert np.abs(qp.astype(np.float64) - ref_q).max() <= 2.0 ** -9 * max(1.0, np.abs(ref_q).max())
+            # selection with the library's approximate query, attention with the real one
+            lab = O.build_label(t["K"], ch, L)
+            sc = O.scores(qp, lab, ch, L, precision=32)
+            idx = np.stack([[O.topk(sc[b, h], k)[0] for h in range(Hkv)] for b in range(B)]).astype(np.int32)
+            ref = O.attend_idx(t["q"], t["K"], t["V"], idx)
+            check_output(outs[l].cpu().numpy(), ref, f"offload+predict layer {l} rep {rep}")
+
+
 # ---------------------------------------------------------------- 4-bit label cache
 def _q4_parity(q, K, V, ch, L, k, what, split=None):
     """Codes and amax bit-exact against the oracle's quantiser; selection identical to the

@@ -146,6 +146,21 @@ def test_append_kv_equals_cache_built_in_one_go():
     assert np.array_equal(kv[:, :, :, 1].view(np.uint16), V.view(np.uint16))
 
 
+def test_predict_query_hand_case_identity_and_linearity():
+    # 2 x 3 projection written out: q0 = 1*1 + 2*(-2) + 0.5*4 = -1, q1 = 0*1 + (-1)*(-2) + 3*4 = 14
+    Wq = np.array([[1, 2, 0.5], [0, -1, 3]], np.float16)
+    x = np.array([[1, -2, 4]], np.float16)
+    assert O.predict_query(x, Wq).tolist() == [[-1.0, 14.0]]
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((3, 16)).astype(np.float16)
+    assert np.array_equal(O.predict_query(x, np.eye(16, dtype=np.float16)), x)   # identity projection
+    W = rng.integers(-2, 3, size=(5, 16)).astype(np.float16)
+    xi = rng.integers(-3, 4, size=(2, 16)).astype(np.float16)                    # integers: exact in fp16
+    got = O.predict_query(np.stack([xi[0], xi[1], xi[0] + xi[1]]), W).astype(np.float64)
+    assert np.array_equal(got[2], got[0] + got[1])
+    assert O.predict_query(x, W).shape == (3, 5)                                 # rows of Wq are output features
+
+
 # ---------------------------------------------------------------- 4-bit label cache
 def _unpack_q4(codes, r):
     """numpy view of the packed codes as int [.., r] (independent of the oracle's unpacking)."""

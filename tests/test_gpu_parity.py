@@ -2,6 +2,8 @@
 by element, on seeded synthetic inputs.  Small/odd shapes span several tiles
 and ragged tails; the BASELINE configurations run at full size in the launch
 configuration the bench times."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -552,6 +554,26 @@ def test_q4_label_cache_full_config(name):
     del t
     torch.cuda.empty_cache()
     print(name, "q4", _q4_parity(q, K, V, ch, w.L, w.k, name + " q4"))
+
+
+# ---------------------------------------------------------------- determinism across processes
+@pytest.mark.parametrize("name", ["C1", "long"])
+def test_second_process_gives_identical_bytes(name):
+    """The same binary and inputs give the same output and index bytes in this process
+    (twice) and in a fresh one."""
+    import subprocess
+    import sys as _sys
+    from tests.determinism_child import digest
+    k3, k4 = ds.ds_tune_get(3), ds.ds_tune_get(4)
+    here = digest(name, k3, k4)
+    ds.ds_tune_set(3, k3); ds.ds_tune_set(4, k4)
+    assert digest(name, k3, k4) == here
+    ds.ds_tune_set(3, k3); ds.ds_tune_set(4, k4)
+    child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "determinism_child.py")
+    res = subprocess.run([_sys.executable, child, name, str(k3), str(k4)], capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0, res.stderr[-2000:]
+    there = [ln.split()[1] for ln in res.stdout.splitlines() if ln.startswith("digest ")]
+    assert there == [here]
 
 
 # ---------------------------------------------------------------- determinism across tuning-independent reruns

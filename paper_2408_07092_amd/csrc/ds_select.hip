@@ -1,16 +1,20 @@
-// Steps 1-2 of Algorithm 1 on gfx950: label-cache scoring and exact per-unit
-// top-k as a radix select, in two launches.
+// Steps 1-2 of Algorithm 1 on gfx950: approximate scoring and exact per-unit
+// top-k as a radix select.
 //
-//   k_score  streams the label cache, forms the binary32 approximate score of
-//            every token, stores it as an ordered 32-bit key and builds a
-//            4096-bin histogram of the keys' top 12 bits per unit.  The last
+//   k_score  streams the label cache (or, in its other modes, the K rows or the
+//            4-bit label cache), forms the binary32 approximate score of every
+//            token, stores it as an ordered 32-bit key and builds a 4096-bin and
+//            a 256-bin histogram of the keys' top bits per unit.  The last
 //            workgroup to finish a unit finds the bin b* that holds the k-th
-//            largest key and clears the histogram for the next call.
+//            largest key and clears the histograms for the next call; for short
+//            units it also settles the exact threshold from the keys.
 //   k_cand   collects the keys of bin b* (the only ones whose fate is open) and
 //            counts, per token chunk, the keys above b*.  The last workgroup of
 //            a unit radix-selects the exact k-th key T among the candidates,
 //            resolves equal keys towards the lowest token index (tcut), and
 //            turns the per-chunk counts into offsets of the ascending index list.
+//            (The default decode path does this inside its attention launch
+//            instead; ds_select and the three-launch shape use k_cand.)
 //   k_compact writes that index list (for callers that only want indices).
 // All counters are integers, so the result does not depend on the order in
 // which workgroups or atomics complete.

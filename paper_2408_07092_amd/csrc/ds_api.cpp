@@ -41,7 +41,12 @@ bool make_plan(const ds_shape_t &s, Plan *p)
 
     int sc = g_tune[0];
     // fewer, larger workgroups: every workgroup pays an arrival atomic and a histogram flush
-    if (sc == 0) sc = (tokens >= (1 << 21)) ? 4096 : (tokens >= (1 << 20)) ? 2048 : 1024;
+    if (sc == 0) {
+        sc = (tokens >= (1 << 21)) ? 4096 : (tokens >= (1 << 20)) ? 2048 : 1024;
+        // enough units to fill the device on their own: one workgroup scores a whole short unit
+        // and takes the threshold bin from its own histogram, with no traffic between workgroups
+        if (p->units >= 256 && s.L <= 8192) sc = (s.L + 255) & ~255;
+    }
     p->sc_chunk = sc;
     p->n_sc = (s.L + sc - 1) / sc;
 

@@ -251,7 +251,8 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
     __syncthreads();
     uint32_t *hu = hist + (size_t)u * kHistBins;
     uint32_t *cu = coarse + (size_t)u * 256;
-    {
+    const bool whole_unit = gridDim.x == 1;  // this workgroup scored every token of the unit
+    if (!whole_unit) {
         // neighbouring lanes add to neighbouring words (a wavefront's atomics that fall into one
         // cache line are served together); coarse bin tid = fine bins 16*tid .. 16*tid+15
         uint32_t c[kHistBins / kWG], cc = 0;
@@ -266,39 +267,53 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
         if (cc) atomicAdd(&cu[tid], cc);
     }
 
-    // ---- last workgroup of the unit: threshold bin (coarse bin first, then its 16 fine bins),
-    // then leave the histograms clean
     DS_TR(3);
-    {
-        const bool last = last_arrival(&ctl[u].arrive_a, gridDim.x, &s_flag);
-        DS_TR(4);
-        if (!last) return;
-    }
-    hist_select<1, true>([&](int bin) { return ld_dev(cu + bin); }, (uint32_t)k_eff, s_w, s_res);
-    const uint32_t cb = s_res[0], rank = s_res[1];
-    if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
-    __syncthreads();
-    DS_TR(5);
-    if (tid == 0) {
-        uint32_t before = 0, bin = 0, krem = 1;
-        for (int i = 0; i < 16; ++i) {
-            if (before + s_fine[i] >= rank) {
-                bin = cb * 16 + 15 - i;
-                krem = rank - before;
-                break;
-            }
-            before += s_fine[i];
+    if (whole_unit) {
+        // The workgroup's own histogram is the unit's: the threshold bin comes straight out of
+        // LDS, nothing goes through the unit histograms in memory and no arrival is counted.
+        hist_select<kHistBins / kWG, true>([&](int bin) { return lh[bin]; }, (uint32_t)k_eff, s_w, s_res);
+        if (tid == 0) {
+            ctl[u].bstar = s_res[0];
+            ctl[u].krem = s_res[1];
+            s_n = 0u;
         }
-        ctl[u].bstar = bin;
-        ctl[u].krem = krem;
-        ctl[u].arrive_a = 0u;
-        s_res[0] = bin;
-        s_res[1] = krem;
-        s_n = 0u;
+        if (!tail_refine) return;
+        // the tail below reads the keys back: wait until this workgroup's own stores are done
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        // ---- last workgroup of the unit: threshold bin (coarse bin first, then its 16 fine
+        // bins), then leave the histograms clean
+        {
+            const bool last = last_arrival(&ctl[u].arrive_a, gridDim.x, &s_flag);
+            DS_TR(4);
+            if (!last) return;
+        }
+        hist_select<1, true>([&](int bin) { return ld_dev(cu + bin); }, (uint32_t)k_eff, s_w, s_res);
+        const uint32_t cb = s_res[0], rank = s_res[1];
+        if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
+        __syncthreads();
+        DS_TR(5);
+        if (tid == 0) {
+            uint32_t before = 0, bin = 0, krem = 1;
+            for (int i = 0; i < 16; ++i) {
+                if (before + s_fine[i] >= rank) {
+                    bin = cb * 16 + 15 - i;
+                    krem = rank - before;
+                    break;
+                }
+                before += s_fine[i];
+            }
+            ctl[u].bstar = bin;
+            ctl[u].krem = krem;
+            ctl[u].arrive_a = 0u;
+            s_res[0] = bin;
+            s_res[1] = krem;
+            s_n = 0u;
+        }
+        for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
+        cu[tid] = 0u;
+        if (!tail_refine) return;
     }
-    for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
-    cu[tid] = 0u;
-    if (!tail_refine) return;
 
     // ---- the same workgroup settles the exact threshold: one pass over the unit's keys (all
     // written through by now) collects the keys of bin b*, which are then radix-selected in LDS.

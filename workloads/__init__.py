@@ -61,6 +61,9 @@ WORKLOADS = {
     "C3": Workload("C3", 1, 32, 32, 128, 65536, 8, 4096, 32, "Llama-2-7B-shaped, L=64K (headline)"),
     "C4a": Workload("C4a", 16, 64, 8, 128, 32768, 8, 2048, 80, "Llama-2-70B-shaped GQA, group 8"),
     "C4b": Workload("C4b", 16, 32, 8, 128, 32768, 8, 2048, 32, "Mixtral-shaped GQA, group 4"),
+    # two corners of the batch x length grid of the paper's label-cache ablation table (appendix):
+    "A1": Workload("A1", 32, 32, 32, 128, 2048, 8, 128, 32, "ablation grid corner: batch 32, 2K tokens"),
+    "A2": Workload("A2", 32, 32, 32, 128, 8192, 8, 512, 32, "ablation grid corner: batch 32, 8K tokens"),
     "C5": Workload("C5", 1, 32, 32, 128, 262144, 8, 16384, 32, "offload-style, K/V in pinned host memory"),
 }
 

@@ -84,6 +84,31 @@ def test_identity_channels_k_eq_L_is_dense():
     check_output(case.gpu_dense(), O.dense_decode(t["q"], t["K"], t["V"], 640), "dense")
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        Hkv = int(rng.choice([1, 2, 3, 5]))
+        G = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        B = int(rng.integers(1, 4))
+        L = int(rng.choice([rng.integers(1, 40), rng.integers(40, 1200), rng.integers(1200, 7000), rng.integers(8200, 14000)]))
+        L_max = L + int(rng.choice([0, 1, 3, 17]))
+        r = int(rng.choice([1, 2, 5, 8, 8, 8, 16, 24]))
+        k = int(max(1, min(L + 2, rng.choice([1, L // 16 + 1, L // 4 + 1, L]))))
+        out.append((B, Hkv * G, Hkv, L, L_max, r, k))
+    return out
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", _random_shapes(14, seed=314159))
+def test_random_shapes(B, Hq, Hkv, L, L_max, r, k):
+    """A seeded draw of shapes (head groups, ragged lengths, padded caches, r and k at
+    both ends of their ranges) through every stage against the oracle."""
+    w = small_workload(B, Hq, Hkv, L, r, k)
+    t = make_layer_numpy(w, L_max=L_max)
+    case = Case(t["q"], t["K"], t["V"], rand_channels(Hkv, 128, r, seed=L + 7 * r), L, k)
+    full_parity(case, check_dense=(L < 3000), what=f"random shape {(B, Hq, Hkv, L, L_max, r, k)}")
+
+
 # ---------------------------------------------------------------- ties
 @pytest.mark.parametrize("L,k,G", [(1200, 100, 1), (5000, 313, 1), (2500, 77, 4)])
 def test_integer_scores_many_exact_ties(L, k, G):

@@ -1,6 +1,6 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
 by element, on seeded synthetic inputs.  Small/odd shapes span several tiles
-and ragged tails; the BASELINE configurations run at full size in the launch
+and ragged tails; the benchmark configurations run at full size in the launch
 configuration the bench times."""
 import os
 

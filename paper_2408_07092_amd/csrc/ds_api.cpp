@@ -51,10 +51,15 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     p->n_sc = (s.L + sc - 1) / sc;
 
     // Launch shape of ds_sparse_decode: units of more than 8K tokens refine the threshold behind
-    // the attention (two launches); shorter units refine it in the scoring launch's tail.
-    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && s.L > (1 << 13));
+    // the attention (two launches); shorter units refine it in the scoring launch's tail -- unless
+    // there are enough of them (256) to fill the device with one workgroup each: such a workgroup
+    // refines and attends a whole unit out of LDS and writes the result itself.
+    const bool one_wg_units = p->units >= 256 && s.L <= 6144;
+    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units));
     int ch = g_tune[1];
-    if (ch == 0 && p->refine_attend) {
+    if (ch == 0 && p->refine_attend && one_wg_units) {
+        ch = (s.L + 255) & ~255;
+    } else if (ch == 0 && p->refine_attend) {
         // every workgroup resident at once (six per CU on the vector path, three on the matrix
         // cores) when chunks of up to 4096 / 6144 tokens allow it
         if (p->G <= 2) {

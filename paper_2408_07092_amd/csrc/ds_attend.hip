@@ -92,8 +92,10 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
     }
 
     auto row_of = [&](int ri) { return (MODE == 0) ? sel[ri] : (MODE == 1) ? (t0 + ri) : ri; };
+    const bool single = gridDim.x == 1;  // the unit's only workgroup writes the result itself
     for (int g0 = 0; g0 < a.G; g0 += GT) {
         float *po = a.part + (((size_t)u * a.G + g0) * a.n_ch + c) * kPartStride;
+        float *od = single ? a.out + ((size_t)u * a.G + g0) * kD : nullptr;
         const _Float16 *q0 = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0) * kD;
         __syncthreads();
         if constexpr (GT >= 4) {
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
             st.init();
             attend_rows_mfma(Ku, Vu, row_bytes, n, row_of, qreg, st, sc_sh[tid >> 6]);
             DS_TR(2);
-            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride);
+            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride, od);
         } else {
             if (tid < GT * 16) {
                 const int g = tid >> 4, p = tid & 15;
@@ -116,12 +118,13 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
             st.init();
             attend_rows<GT>(Ku, Vu, row_bytes, n, row_of, qsh, st);
             DS_TR(2);
-            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride);
+            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
         }
     }
 
     // ---- last workgroup of the unit: combine the chunk partials of every head of the group
     DS_TR(3);
+    if (single) return;
     {
         const bool last = last_arrival(&a.ctl_rw[u].arrive_c, gridDim.x, &s_flag);
         DS_TR(4);
@@ -241,12 +244,15 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
         n_def += (int)(total & 0xffffu);
         n_cand += total >> 16;
     }
-    if (tid == 0) {
+    // A unit with this one workgroup keeps everything in LDS: no candidate list in memory, no
+    // arrival, nothing to publish.
+    const bool single = gridDim.x == 1;
+    if (!single && tid == 0) {
         s_base = n_cand ? __hip_atomic_fetch_add(&ctl->ncand, n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
         if (a.idx_out) st_dev(a.ndef + (size_t)u * a.n_ch + c, (uint32_t)n_def);
     }
     __syncthreads();
-    {
+    if (!single) {
         // (a unit has L candidates at most; a base beyond that means the workspace was not cleared)
         const uint32_t base = s_base;
         if (base + n_cand <= (uint32_t)a.L) {
@@ -259,7 +265,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
         }
     }
     DS_TR(1);
-    bool have_T = last_arrival(&ctl->arrive_b, gridDim.x, &s_flag);
+    bool have_T = single ? true : last_arrival(&ctl->arrive_b, gridDim.x, &s_flag);
     DS_TR(2);
     uint32_t T = 0;
     int tcut = 0x7fffffff;
@@ -267,12 +273,21 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
         // ---- the unit is complete: exact k-th key among the candidates (10 + 10 key bits), ties
         // to the lowest token (4 + 10 + 10 index bits; tokens are below 2^24).  Up to 2048
         // candidates stay in registers; beyond that every pass re-reads the list.
-        const uint32_t n = min(ld_dev(&ctl->ncand), (uint32_t)a.L);
+        const uint32_t n = single ? n_cand : min(ld_dev(&ctl->ncand), (uint32_t)a.L);
         const bool in_regs = n <= 8u * kWG;
+        // candidate i of the unit: out of the list in memory, or (single workgroup) the i-th
+        // staged token of this chunk
+        auto cand_at = [&](uint32_t i) {
+            if (single) {
+                const int lt = sel[a.ch - 1 - (int)i];
+                return make_uint2(keys_sh[lt], (uint32_t)(t0 + lt));
+            }
+            return ld_dev(cu + i);
+        };
         uint2 ce[8];
         if (in_regs && n) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) ce[x] = ld_dev(cu + min((uint32_t)(tid + x * kWG), n - 1));
+            for (int x = 0; x < 8; ++x) ce[x] = cand_at(min((uint32_t)(tid + x * kWG), n - 1));
         }
         auto each = [&](auto f) {
             if (in_regs) {
@@ -280,7 +295,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
                 for (int x = 0; x < 8; ++x)
                     if ((uint32_t)(tid + x * kWG) < n) f(ce[x]);
             } else {
-                for (uint32_t i = tid; i < n; i += kWG) f(ld_dev(cu + i));
+                for (uint32_t i = tid; i < n; i += kWG) f(cand_at(i));
             }
         };
         DS_TR(8);
@@ -311,7 +326,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             tcut = (int)((prefix << 10) | s_res[0]);
             __syncthreads();
         }
-        if (a.idx_out) {
+        if (a.idx_out && !single) {
             // selected tokens per chunk = keys above b* + selected candidates; prefix -> offsets
             for (int i = tid; i < a.n_ch; i += kWG) cnt[i] = ld_dev(a.ndef + (size_t)u * a.n_ch + i);
             __syncthreads();
@@ -332,7 +347,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
-        if (tid == 0) {
+        if (!single && tid == 0) {
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             st_dev(&ctl->ncand, 0u);
             st_dev(&ctl->arrive_b, 0u);
@@ -375,7 +390,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             have_T = true;
         }
         DS_TR(4);
-        const uint32_t off = a.idx_out ? ld_dev(a.offs_rw + (size_t)u * a.n_ch + c) : 0u;
+        const uint32_t off = (a.idx_out && !single) ? ld_dev(a.offs_rw + (size_t)u * a.n_ch + c) : 0u;
         int32_t *io = a.idx_out ? a.idx_out + (size_t)u * a.k : nullptr;
         int all_base = 0;
         for (int p = 0; p < n_pass; ++p) {
@@ -412,6 +427,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
 
     for (int g0 = 0; g0 < a.G; g0 += GT) {
         float *po = a.part + (((size_t)u * a.G + g0) * a.n_ch + c) * kPartStride;
+        float *od = single ? a.out + ((size_t)u * a.G + g0) * kD : nullptr;
         const _Float16 *q0 = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0) * kD;
         __syncthreads();
         if constexpr (GT >= 4) {
@@ -424,7 +440,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             if (g0 == 0) { DS_TR(3); settle(); }
             attend_rows_mfma(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qreg, st, sc_sh[tid >> 6]);
             DS_TR(5);
-            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride);
+            wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride, od);
         } else {
             if (tid < GT * 16) {
                 const int g = tid >> 4, p = tid & 15;
@@ -437,11 +453,12 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             if (g0 == 0) { DS_TR(3); settle(); }
             attend_rows<GT>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
             DS_TR(5);
-            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride);
+            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
         }
     }
 
     // ---- last workgroup of the unit: merge the chunk partials, leave the control words clean
+    if (single) return;
     {
         const bool last = last_arrival(&ctl->arrive_c, gridDim.x, &s_flag);
         DS_TR(6);

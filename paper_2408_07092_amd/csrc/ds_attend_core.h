@@ -119,10 +119,13 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 // Second half of a workgroup's partial: the four wavefronts' states in
 // wpart[wave][head] = {m, l, -, -, acc[128]} (LDS) are merged in wave order and
 // written as one partial per head to po + g * head_stride with device-scope
-// stores.  Starts with a barrier; callers put a barrier between two uses of wpart.
+// stores.  With out_direct (a unit that has this one workgroup only) the final
+// result acc / l goes to out_direct + g * kD instead; that is what merging the
+// single partial would give, bit for bit.
+// Starts with a barrier; callers put a barrier between two uses of wpart.
 template <int GH>
 __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride], int n_heads, float *po,
-                                                 size_t head_stride)
+                                                 size_t head_stride, float *out_direct = nullptr)
 {
     const int tid = threadIdx.x;
     __syncthreads();
@@ -141,11 +144,15 @@ __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride]
                     A += f * wpart[w][g][4 + tid];
                     Ls += f * wpart[w][g][1];
                 }
-                float *pg = po + (size_t)g * head_stride;
-                st_dev(pg + 4 + tid, A);
-                if (tid == 0) {
-                    st_dev(pg + 0, M);
-                    st_dev(pg + 1, Ls);
+                if (out_direct) {
+                    out_direct[(size_t)g * kD + tid] = A / Ls;
+                } else {
+                    float *pg = po + (size_t)g * head_stride;
+                    st_dev(pg + 4 + tid, A);
+                    if (tid == 0) {
+                        st_dev(pg + 0, M);
+                        st_dev(pg + 1, Ls);
+                    }
                 }
             }
         }
@@ -157,7 +164,7 @@ __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride]
 template <int GT>
 __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
                                                  float (*wpart)[GT][kPartStride], float *po,
-                                                 size_t head_stride)
+                                                 size_t head_stride, float *out_direct = nullptr)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
@@ -185,7 +192,7 @@ __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
             }
         }
     }
-    wg_combine_store<GT>(wpart, GT, po, head_stride);
+    wg_combine_store<GT>(wpart, GT, po, head_stride, out_direct);
 }
 
 // ---------------------------------------------------------------- matrix-core path for query groups
@@ -290,7 +297,8 @@ __device__ __forceinline__ void attend_rows_mfma(const char *Ku, const char *Vu,
 // Writes the calling wavefront's state to wpart[wave][head] and runs the workgroup combine.
 template <int GH>
 __device__ __forceinline__ void wg_store_partial_mfma(const MfmaState &st, float (*wpart)[GH][kPartStride],
-                                                      int n_heads, float *po, size_t head_stride)
+                                                      int n_heads, float *po, size_t head_stride,
+                                                      float *out_direct = nullptr)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lo = lane & 15, hi = lane >> 4;
@@ -309,7 +317,7 @@ __device__ __forceinline__ void wg_store_partial_mfma(const MfmaState &st, float
             for (int e = 0; e < 8; ++e) wpart[wave][head][4 + 8 * lo + e] = st.O[e][rr];
         }
     }
-    wg_combine_store<GH>(wpart, n_heads, po, head_stride);
+    wg_combine_store<GH>(wpart, n_heads, po, head_stride, out_direct);
 }
 
 // Combines the n_ch chunk partials of each of the G heads of one unit:

@@ -386,6 +386,12 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     if (p.refine_attend && refine_attend_ok(p)) {
         // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
         // behind the attention over the rows that are selected either way
+        // one workgroup per unit and a plain fp16 label cache of 8 or 16 channels: that workgroup
+        // scores the unit itself -- one launch, keys never leave LDS (knob 4 = 1 keeps two launches)
+        if (p.n_ch == 1 && src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16) && tune_get(4) != 1) {
+            DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride, label, channels));
+            return DS_OK;
+        }
         DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, src));
         DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
         return DS_OK;

@@ -36,6 +36,9 @@ struct AttendArgs {
     uint32_t *ndef;      // [units][n_ch] keys above bin b* per chunk
     uint32_t *offs_rw;   // [units][n_ch] offset of the chunk in the ascending index list
     uint32_t spin_limit;
+    // k_refine_attend with the scoring done in the same launch (one workgroup per unit)
+    const _Float16 *label;     // [units][L_max][r]
+    const int32_t *channels;   // [Hkv][r]
 };
 
 // MODE 0: rows = tokens of the chunk that pass the selection predicate
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // workgroups get to run as long as one XCD can hold its share (every eighth) of
 // the n_ch of them (checked on the host).  The wait is bounded as well: on expiry
 // the unit's error word is raised and the workgroup carries on without candidates.
-template <int GT>
+template <int GT, int SMODE>
 __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(AttendArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
@@ -189,11 +192,78 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     uint2 *ready = reinterpret_cast<uint2 *>(&ctl->cnt_a);  // {T, tie cut | 1<<31}
     DS_TR(0);
 
-    // ---- 1. classify the chunk's keys against bin b*
-    const uint32_t bstar = ctl->bstar;
-    const uint32_t lo_key = bstar << kKeyShift;
-    {
+    uint32_t bstar, krem_unit;
+    if constexpr (SMODE > 0) {
+        // ---- 0. (one workgroup per unit, r = SMODE) Algorithm 1 steps 1-2 right here: stream the
+        // unit's label rows, keys go to LDS only, the threshold bin comes out of this workgroup's
+        // own histogram.  Same arithmetic and order as k_score.
+        constexpr int NV = SMODE / 8;
+        __shared__ uint32_t hist_sh[kHistBins];
+        __shared__ float qs_sh[SMODE];
+        __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
+        const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
+        half8 v[8][NV];
+        auto issue = [&](int tb) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, a.L - 1) * SMODE);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) v[i][j] = row[j];
+            }
+        };
+        int c_q = 0;
+        if (tid < SMODE) c_q = a.channels[h * SMODE + tid];
+        float a_q = 0.0f;
+        for (int g0 = 0; g0 < a.G; g0 += 8) {
+            const int ng = min(8, a.G - g0);
+            if (g0) __syncthreads();
+            if (tid >= 128 && tid - 128 < ng * 16) {
+                const int g = (tid - 128) >> 4, pp = (tid - 128) & 15;
+                const _Float16 *src = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0 + g) * kD + pp * 8;
+                *reinterpret_cast<uint4 *>(&qrow_sh[g][pp * 8]) = *reinterpret_cast<const uint4 *>(src);
+            }
+            if (g0 == 0) {
+                issue(tid);
+                __builtin_amdgcn_sched_barrier(0);
+                for (int i = tid; i < kHistBins; i += kWG) hist_sh[i] = 0u;
+            }
+            __syncthreads();
+            if (tid < SMODE)
+                for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
+        }
+        if (tid < SMODE) qs_sh[tid] = a_q;
+        __syncthreads();
+        float qs[SMODE];
+#pragma unroll
+        for (int j = 0; j < SMODE; ++j) qs[j] = qs_sh[j];
+        for (int tb = tid; tb < a.L;) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int j = 0; j < NV; ++j)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
+                const int t = tb + i * kWG;
+                if (t < a.L) {
+                    const uint32_t key = score_key(acc);
+                    keys_sh[t] = key;
+                    atomicAdd(&hist_sh[key >> kKeyShift], 1u);
+                }
+            }
+            tb += kWG * 8;
+            if (tb < a.L) issue(tb);
+        }
+        __syncthreads();
+        hist_select<kHistBins / kWG, true>([&](int bin) { return hist_sh[bin]; }, (uint32_t)a.k_eff, s_w, s_res);
+        bstar = s_res[0];
+        krem_unit = s_res[1];
+        __syncthreads();
+    } else {
+        // ---- 1. the chunk's keys come from the scoring launch, with the unit's threshold bin;
         // all of the thread's key loads are in flight together; the keys then live in LDS
+        bstar = ctl->bstar;
+        krem_unit = ctl->krem;
         uint4 kv[kMaxPass];
 #pragma unroll
         for (int p = 0; p < kMaxPass; ++p) {
@@ -207,6 +277,8 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             if (p < n_pass && t0 + lt < t1) *reinterpret_cast<uint4 *>(keys_sh + lt) = kv[p];
         }
     }
+    // ---- classify the chunk's keys against bin b*
+    const uint32_t lo_key = bstar << kKeyShift;
     // own_keys(p): the thread's four keys of pass p (zeros past the end of the chunk)
     auto own_keys = [&](int p, uint32_t (&k4)[4]) {
         const int lt = (p * kWG + tid) * 4;
@@ -299,7 +371,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             }
         };
         DS_TR(8);
-        uint32_t krem = ctl->krem;
+        uint32_t krem = krem_unit;
         svc_radix_pass<4, true>(each, [](uint2) { return true; },
                                 [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
         const uint32_t pre22 = (bstar << 10) | s_res[0];
@@ -538,9 +610,12 @@ bool refine_attend_ok(const Plan &p)
     return (p.n_ch + 7) / 8 <= per_xcd;
 }
 
+// score_label / score_channels: non-null to run the scoring in the same launch (the plan must
+// have one chunk per unit and r must be 8 or 16); otherwise the keys and the threshold bin of a
+// preceding k_score launch are read from the workspace.
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
-                                int kv_stride)
+                                int kv_stride, const void *score_label, const int32_t *score_channels)
 {
     AttendArgs a{};
     a.q = static_cast<const _Float16 *>(q);
@@ -560,15 +635,26 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
     a.spin_limit = 1u << 21;
     a.kv_stride = kv_stride;
+    a.label = static_cast<const _Float16 *>(score_label);
+    a.channels = score_channels;
+    const int smode = score_label ? s.r : 0;
+    if (smode && (p.n_ch != 1 || (s.r != 8 && s.r != 16))) return hipErrorInvalidValue;
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
+#define DS_RA(GTV)                                                                                     \
+    do {                                                                                               \
+        if (smode == 8) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 8>), grid, dim3(kWG), shmem, st, a);   \
+        else if (smode == 16) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 16>), grid, dim3(kWG), shmem, st, a); \
+        else DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 0>), grid, dim3(kWG), shmem, st, a);    \
+    } while (0)
     switch (pick_gt(a.G)) {
-    case 16: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<16>), grid, dim3(kWG), shmem, st, a); break;
-    case 8: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<8>), grid, dim3(kWG), shmem, st, a); break;
-    case 4: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<4>), grid, dim3(kWG), shmem, st, a); break;
-    case 2: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<2>), grid, dim3(kWG), shmem, st, a); break;
-    default: DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1>), grid, dim3(kWG), shmem, st, a); break;
+    case 16: DS_RA(16); break;
+    case 8: DS_RA(8); break;
+    case 4: DS_RA(4); break;
+    case 2: DS_RA(2); break;
+    default: DS_RA(1); break;
     }
+#undef DS_RA
     return hipGetLastError();
 }
 

@@ -117,7 +117,8 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
 bool refine_attend_ok(const Plan &p);
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
-                                int kv_stride = kD);
+                                int kv_stride = kD, const void *score_label = nullptr,
+                                const int32_t *score_channels = nullptr);
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,

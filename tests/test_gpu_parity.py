@@ -17,20 +17,26 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend"], autouse=True)
+@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "auto"],
+                autouse=True)
 def decode_path(request):
     """Every test runs on every implementation of ds_sparse_decode: the single
     launch (workers + reducers), the co-resident two-launch path, the
     three-launch path with the exact threshold settled either in the scoring
-    launch's tail or in a candidate launch of its own, and scoring followed by
-    the launch that refines the threshold behind the attention."""
-    mode, refine = {"one_launch": (2, 0), "two_launch": (3, 0), "score_tail": (1, 2),
-                    "cand_launch": (1, 1), "refine_attend": (4, 1)}[request.param]
+    launch's tail or in a candidate launch of its own, scoring followed by the
+    launch that refines the threshold behind the attention, that launch with one
+    workgroup per unit doing the scoring as well (chunks of 6144 tokens: units up
+    to that length), and the library's own choice."""
+    mode, refine, chunk = {"one_launch": (2, 0, 0), "two_launch": (3, 0, 0), "score_tail": (1, 2, 0),
+                           "cand_launch": (1, 1, 0), "refine_attend": (4, 1, 0), "unit_fused": (4, 0, 6144),
+                           "auto": (0, 0, 0)}[request.param]
     ds.ds_tune_set(3, mode)
     ds.ds_tune_set(4, refine)
+    ds.ds_tune_set(1, chunk)
     yield request.param
     ds.ds_tune_set(3, 0)
     ds.ds_tune_set(4, 0)
+    ds.ds_tune_set(1, 0)
 
 
 def rand_channels(Hkv, d, r, seed, sort=True):
@@ -589,13 +595,13 @@ def test_second_process_gives_identical_bytes(name):
     import subprocess
     import sys as _sys
     from tests.determinism_child import digest
-    k3, k4 = ds.ds_tune_get(3), ds.ds_tune_get(4)
-    here = digest(name, k3, k4)
-    ds.ds_tune_set(3, k3); ds.ds_tune_set(4, k4)
-    assert digest(name, k3, k4) == here
-    ds.ds_tune_set(3, k3); ds.ds_tune_set(4, k4)
+    k3, k4, k1 = ds.ds_tune_get(3), ds.ds_tune_get(4), ds.ds_tune_get(1)
+    here = digest(name, k3, k4, k1)
+    assert digest(name, k3, k4, k1) == here
+    ds.ds_tune_set(3, k3); ds.ds_tune_set(4, k4); ds.ds_tune_set(1, k1)
     child = os.path.join(os.path.dirname(os.path.abspath(__file__)), "determinism_child.py")
-    res = subprocess.run([_sys.executable, child, name, str(k3), str(k4)], capture_output=True, text=True, timeout=240)
+    res = subprocess.run([_sys.executable, child, name, str(k3), str(k4), str(k1)], capture_output=True, text=True,
+                         timeout=240)
     assert res.returncode == 0, res.stderr[-2000:]
     there = [ln.split()[1] for ln in res.stdout.splitlines() if ln.startswith("digest ")]
     assert there == [here]

@@ -291,7 +291,7 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 256, <= 6144)
  *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
  *   knob 3: how ds_sparse_decode is launched: 0 = automatic (4 for units of more than 8K
- *           tokens and for 256 or more units of up to 6144 tokens, else 1), 1 = three launches
+ *           tokens, of up to 4096 tokens, or 256 or more of up to 6144 tokens; else 1), 1 = three launches
  *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
  *           workgroups when the shape and the device allow it (else three launches),
  *           3 = two launches: that co-resident launch up to the threshold candidates, then

@@ -51,10 +51,12 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     p->n_sc = (s.L + sc - 1) / sc;
 
     // Launch shape of ds_sparse_decode: units of more than 8K tokens refine the threshold behind
-    // the attention (two launches); shorter units refine it in the scoring launch's tail -- unless
-    // there are enough of them (256) to fill the device with one workgroup each: such a workgroup
-    // refines and attends a whole unit out of LDS and writes the result itself.
-    const bool one_wg_units = p->units >= 256 && s.L <= 6144;
+    // the attention (two launches).  Units of up to 4K tokens -- up to 6144 when there are enough
+    // of them (256) to fill the device -- get one workgroup each, which scores, refines and attends
+    // the whole unit out of LDS and writes the result itself: everything between workgroups (keys
+    // in memory, histograms, arrival counting, partials) costs more than it spreads at that size.
+    // What lies between refines the threshold in the scoring launch's tail.
+    const bool one_wg_units = s.L <= 4096 || (p->units >= 256 && s.L <= 6144);
     p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units));
     int ch = g_tune[1];
     if (ch == 0 && p->refine_attend && one_wg_units) {

@@ -288,10 +288,12 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
 /*
  * Launch-shape knobs, for sweeps (defaults are chosen from the shape):
  *   knob 0: tokens per workgroup in the scoring kernel   (0 = automatic; multiple of 256)
- *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 256, <= 6144)
+ *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 256, <= 16384;
+ *           the candidate launch of shape 1 and ds_select take up to 6144)
  *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
  *   knob 3: how ds_sparse_decode is launched: 0 = automatic (4 for units of more than 8K
- *           tokens, of up to 4096 tokens, or 256 or more of up to 6144 tokens; else 1), 1 = three launches
+ *           tokens and for units short enough for one workgroup each: up to 4K tokens, up to
+ *           8K when there are 256 units or more; else 1), 1 = three launches
  *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
  *           workgroups when the shape and the device allow it (else three launches),
  *           3 = two launches: that co-resident launch up to the threshold candidates, then

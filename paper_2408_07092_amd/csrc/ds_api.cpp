@@ -31,7 +31,7 @@ static bool shape_ok(const ds_shape_t &s, bool need_rk)
     return true;
 }
 
-bool make_plan(const ds_shape_t &s, Plan *p)
+bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
 {
     if (!shape_ok(s, true)) return false;
     p->units = s.B * s.Hkv;
@@ -51,13 +51,19 @@ bool make_plan(const ds_shape_t &s, Plan *p)
     p->n_sc = (s.L + sc - 1) / sc;
 
     // Launch shape of ds_sparse_decode: units of more than 8K tokens refine the threshold behind
-    // the attention (two launches).  Units of up to 4K tokens -- up to 6144 when there are enough
-    // of them (256) to fill the device -- get one workgroup each, which scores, refines and attends
-    // the whole unit out of LDS and writes the result itself: everything between workgroups (keys
-    // in memory, histograms, arrival counting, partials) costs more than it spreads at that size.
-    // What lies between refines the threshold in the scoring launch's tail.
-    const bool one_wg_units = s.L <= 4096 || (p->units >= 256 && s.L <= 6144);
-    p->refine_attend = g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units));
+    // the attention (two launches).  Short units get one workgroup each, which refines and attends
+    // the whole unit out of LDS and writes the result itself (and scores it too when the label
+    // cache is plain fp16 with 8 or 16 channels): everything between workgroups -- keys in memory,
+    // histograms, arrival counting, partials -- costs more than it spreads at that size.  "Short"
+    // is 4K tokens; 8K when there are enough units (256) to fill the device; 16K for a workgroup
+    // that scores its unit itself, single heads or pairs, with 192 units or more (one 96 KiB
+    // workgroup per CU).  What lies between refines the threshold in the scoring launch's tail.
+    const bool one_wg_units =
+        purpose != PLAN_SELECT &&
+        (s.L <= 4096 || (p->units >= 256 && s.L <= 8192) ||
+         (purpose == PLAN_DECODE_SCORING && p->units >= 192 && p->G <= 2 && s.L <= 16384));
+    p->refine_attend = purpose != PLAN_SELECT &&
+                       (g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units)));
     int ch = g_tune[1];
     if (ch == 0 && p->refine_attend && one_wg_units) {
         ch = (s.L + 255) & ~255;
@@ -322,9 +328,11 @@ size_t ds_workspace_bytes(const ds_shape_t *shape)
     Plan p;
     DensePlan dp, rp;
     size_t need = 0;
-    if (make_plan(*shape, &p)) {
-        need = std::max(need, p.total);
-        if (make_dense_plan(*shape, p.k_eff, &rp)) need = std::max(need, rp.total);
+    for (PlanFor purpose : {PLAN_SELECT, PLAN_DECODE, PLAN_DECODE_SCORING}) {
+        if (make_plan(*shape, &p, purpose)) {
+            need = std::max(need, p.total);
+            if (make_dense_plan(*shape, p.k_eff, &rp)) need = std::max(need, rp.total);
+        }
     }
     if (make_dense_plan(*shape, shape->L, &dp)) need = std::max(need, dp.total);
     return need;
@@ -341,11 +349,11 @@ ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *str
 
 static ds_status_t select_common(const void *q, const void *label, const int32_t *channels,
                                  void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
-                                 Plan *p)
+                                 Plan *p, PlanFor purpose = PLAN_SELECT)
 {
     if (!q || !label || !channels || !workspace || !shape) return DS_ERR_NULL;
     if (!shape_ok(*shape, true)) return DS_ERR_SHAPE;
-    if (!make_plan(*shape, p)) return DS_ERR_UNSUPPORTED;
+    if (!make_plan(*shape, p, purpose)) return DS_ERR_UNSUPPORTED;
     if (!aligned(q, 16) || !aligned(label, 16) || !aligned(workspace, 16)) return DS_ERR_ALIGN;
     if (workspace_bytes < p->total) return DS_ERR_WORKSPACE;
     return DS_OK;
@@ -374,7 +382,12 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
-    ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p);
+    // a workgroup that has a unit to itself can score it too when the labels are plain fp16 with
+    // 8 or 16 channels (knob 4 = 1 keeps the separate scoring launch)
+    const bool may_score = shape && src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16) &&
+                           tune_get(4) != 1;
+    ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p,
+                                   may_score ? PLAN_DECODE_SCORING : PLAN_DECODE);
     if (rc != DS_OK) return rc;
     if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
         return DS_ERR_ALIGN;
@@ -385,12 +398,12 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
     }
-    if (p.refine_attend && refine_attend_ok(p)) {
-        // scoring leaves keys and the threshold bin; one more launch settles the exact threshold
-        // behind the attention over the rows that are selected either way
-        // one workgroup per unit and a plain fp16 label cache of 8 or 16 channels: that workgroup
-        // scores the unit itself -- one launch, keys never leave LDS (knob 4 = 1 keeps two launches)
-        if (p.n_ch == 1 && src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16) && tune_get(4) != 1) {
+    // one workgroup per unit that may score: one launch, keys never leave LDS
+    const bool scores_itself = p.n_ch == 1 && may_score;
+    if (p.refine_attend && refine_attend_ok(p, scores_itself)) {
+        // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
+        // threshold behind the attention over the rows that are selected either way
+        if (scores_itself) {
             DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride, label, channels));
             return DS_OK;
         }
@@ -581,7 +594,7 @@ ds_status_t ds_tune_set(int knob, int value)
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 1 && (value % 256 != 0 || value > 6144)) return DS_ERR_SHAPE;
+        if (knob == 1 && (value % 256 != 0 || value > 16384)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 3 && value > 4) return DS_ERR_SHAPE;
         if (knob == 4 && value > 2) return DS_ERR_SHAPE;

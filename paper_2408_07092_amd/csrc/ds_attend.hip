@@ -161,8 +161,8 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // workgroups get to run as long as one XCD can hold its share (every eighth) of
 // the n_ch of them (checked on the host).  The wait is bounded as well: on expiry
 // the unit's error word is raised and the workgroup carries on without candidates.
-template <int GT, int SMODE>
-__global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(AttendArgs a)
+template <int GT, int SMODE, int RPS = 4>
+__global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
     uint32_t *keys_sh = dyn_sh;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     const int u = blockIdx.y, c = blockIdx.x;
     const int b = u / a.Hkv, h = u % a.Hkv;
     const int t0 = c * a.ch, t1 = min(a.L, t0 + a.ch);
-    constexpr int kMaxPass = 6;                              // ch <= 6144
+    constexpr int kMaxPass = 8;                              // ch <= 8192
     const int n_pass = (t1 - t0 + kWG * 4 - 1) / (kWG * 4);  // <= kMaxPass
     const uint32_t *ku = a.keys + (size_t)u * a.key_stride;
     uint2 *cu = a.cand + (size_t)u * a.L;
@@ -432,10 +432,11 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
     const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * a.kv_stride);
     const uint32_t row_bytes = 2 * a.kv_stride;
     int n_sel = 0;
-    // First the definite rows that fill whole rounds of the four wavefronts (64 rows a round);
-    // the rest of them joins the selected candidates in one list, so that at most one round of
-    // the workgroup runs partly empty.
-    const int n_first = n_def & ~63;
+    // First the definite rows that fill whole rounds of the four wavefronts (64 rows a round, or
+    // 16 * RPS on the vector path); the rest of them joins the selected candidates in one list, so
+    // that at most one round of the workgroup runs partly empty.
+    constexpr int kRound = (GT >= 4) ? 64 : 16 * RPS;
+    const int n_first = (n_def / kRound) * kRound;
     auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };
     auto row_rest = [&](int ri) { return t0 + (int)sel[n_first + ri]; };
     // After the definite rows of the first pass: fetch (T, tie cut), append the selected candidates
@@ -521,9 +522,9 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 4 : 3)) void k_refine_attend(Attend
             __syncthreads();
             RowState<GT> st;
             st.init();
-            attend_rows<GT>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
+            attend_rows<GT, RPS>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
             if (g0 == 0) { DS_TR(3); settle(); }
-            attend_rows<GT>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
+            attend_rows<GT, RPS>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
             DS_TR(5);
             wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
         }
@@ -597,9 +598,11 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
 // Whether k_refine_attend can take this plan: chunks of at most 6144 tokens (six
 // passes of four keys per thread, 16-bit row offsets), and room on one XCD for its
 // share (every eighth workgroup) of a unit's n_ch workgroups at a time.
-bool refine_attend_ok(const Plan &p)
+bool refine_attend_ok(const Plan &p, bool scores_itself)
 {
-    if (p.ch > 6144 || (p.ch & 3)) return false;
+    // keys loaded from memory come in at most eight passes of 1024; a workgroup that scores its
+    // unit itself writes them to LDS directly (16-bit row offsets: up to 16384 tokens tried)
+    if (p.ch > (scores_itself ? 16384 : 8192) || (p.ch & 3)) return false;
     static int per_xcd = 0;
     if (!per_xcd) {
         hipDeviceProp_t prop;
@@ -641,12 +644,37 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     if (smode && (p.n_ch != 1 || (s.r != 8 && s.r != 16))) return hipErrorInvalidValue;
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
+    // more than 64 KiB of dynamic LDS has to be asked for once per kernel
+#define DS_RA_ATTR(KERNEL)                                                                             \
+    do {                                                                                               \
+        static bool done = false;                                                                      \
+        if (shmem > (64u << 10) && !done) {                                                            \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&KERNEL),                           \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 << 10) != hipSuccess) \
+                return hipErrorInvalidValue;                                                           \
+            done = true;                                                                               \
+        }                                                                                              \
+    } while (0)
 #define DS_RA(GTV)                                                                                     \
     do {                                                                                               \
+        if (smode == 8) DS_RA_ATTR((k_refine_attend<GTV, 8>));                                          \
+        else if (smode == 16) DS_RA_ATTR((k_refine_attend<GTV, 16>));                                   \
+        else DS_RA_ATTR((k_refine_attend<GTV, 0>));                                                     \
         if (smode == 8) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 8>), grid, dim3(kWG), shmem, st, a);   \
         else if (smode == 16) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 16>), grid, dim3(kWG), shmem, st, a); \
         else DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 0>), grid, dim3(kWG), shmem, st, a);    \
     } while (0)
+    if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10)) {
+        // the workgroup has a CU to itself (LDS): sixteen rows per slot in flight
+        if (smode == 8) {
+            DS_RA_ATTR((k_refine_attend<1, 8, 16>));
+            DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1, 8, 16>), grid, dim3(kWG), shmem, st, a);
+        } else {
+            DS_RA_ATTR((k_refine_attend<1, 16, 16>));
+            DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1, 16, 16>), grid, dim3(kWG), shmem, st, a);
+        }
+        return hipGetLastError();
+    }
     switch (pick_gt(a.G)) {
     case 16: DS_RA(16); break;
     case 8: DS_RA(8); break;
@@ -655,6 +683,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     default: DS_RA(1); break;
     }
 #undef DS_RA
+#undef DS_RA_ATTR
     return hipGetLastError();
 }
 

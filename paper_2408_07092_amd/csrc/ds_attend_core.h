@@ -58,58 +58,65 @@ struct RowState {
     }
 };
 
-// The calling wavefront's share of the workgroup's n rows: rows wave*16 + 64*i ..
+// The calling wavefront's share of the workgroup's n rows: with RPS rows per 16-lane slot in
+// flight, rows wave*4*RPS + 16*RPS*i ..  (RPS = 4: 64 rows of the workgroup per round trip and
+// 8 loads per lane; larger RPS for a workgroup that has a CU -- and its registers -- to itself).
 // row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
 // Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
-template <int GT, class RowOf>
+template <int GT, int RPS = 4, class RowOf>
 __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
                                             RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
-    for (int r0 = wave * 16; r0 < n; r0 += 64) {
-        // all eight row loads of the pass are issued before the first use; lanes past the
+    for (int r0 = wave * 4 * RPS; r0 < n; r0 += 16 * RPS) {
+        // all row loads of the pass are issued before the first use; lanes past the
         // end re-read the last row of the list (in bounds) and mask its score below
-        half8 kr[4], vr[4];
-        bool ok[4];
-        uint32_t off[4];
+        half8 kr[RPS], vr[RPS];
+        bool ok[RPS];
+        uint32_t off[RPS];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < RPS; ++i) {
             const int want = r0 + i * 4 + slot;
             ok[i] = want < n;
             off[i] = (uint32_t)row_of(min(want, n - 1)) * row_bytes + (uint32_t)part * 16u;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < RPS; ++i) {
             kr[i] = *reinterpret_cast<const half8 *>(Ku + off[i]);
             vr[i] = *reinterpret_cast<const half8 *>(Vu + off[i]);
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the eight loads ahead of the arithmetic
+        __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the arithmetic
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
-            float s[4];
+            // the rows of a slot are folded into its state four at a time, in row order, so that
+            // the result does not depend on RPS
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                s[i] = row16_sum(dot8(qv, kr[i])) * kScaleLog2;
-                if (!ok[i]) s[i] = kNegInf;
-            }
-            // a slot may have no valid row yet (m stays -inf); slot 0 always has one here
-            const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-            const float mn = fmaxf(st.m[g], mx);
-            if (mn != kNegInf) {
-                const float sc = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mn);
-                st.m[g] = mn;
-                st.l[g] *= sc;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) st.acc[g][j] *= sc;
+            for (int i0 = 0; i0 < RPS; i0 += 4) {
+                float s[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(s[i] - mn);  // 2^-inf = 0 for masked rows
-                    st.l[g] += p;
+                    s[i] = row16_sum(dot8(qv, kr[i0 + i])) * kScaleLog2;
+                    if (!ok[i0 + i]) s[i] = kNegInf;
+                }
+                // a slot may have no valid row yet (m stays -inf); slot 0 always has one here
+                const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+                const float mn = fmaxf(st.m[g], mx);
+                if (mn != kNegInf) {
+                    const float sc = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mn);
+                    st.m[g] = mn;
+                    st.l[g] *= sc;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        st.acc[g][j] = __builtin_fmaf(p, (float)vr[i][j], st.acc[g][j]);
+                    for (int j = 0; j < 8; ++j) st.acc[g][j] *= sc;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float p = __builtin_amdgcn_exp2f(s[i] - mn);  // 2^-inf = 0 for masked rows
+                        st.l[g] += p;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            st.acc[g][j] = __builtin_fmaf(p, (float)vr[i0 + i][j], st.acc[g][j]);
+                    }
                 }
             }
         }

@@ -92,7 +92,10 @@ struct ScoreSrc {
     const float *amax = nullptr;  // SRC_Q4: [units][r]
 };
 
-bool make_plan(const ds_shape_t &s, Plan *p);
+// What the plan is for: the split select call (and anything that runs the candidate launch), a
+// decode call, or a decode call whose single workgroup per unit may do the scoring itself.
+enum PlanFor { PLAN_SELECT = 0, PLAN_DECODE = 1, PLAN_DECODE_SCORING = 2 };
+bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose = PLAN_SELECT);
 bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);
 bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f);
 size_t fused_workspace_bytes(const ds_shape_t &s, const Plan &p);
@@ -114,7 +117,7 @@ hipError_t launch_compact(void *ws, int32_t *idx_out, const Plan &p, const ds_sh
 hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                                 hipStream_t st, int kv_stride = kD);
-bool refine_attend_ok(const Plan &p);
+bool refine_attend_ok(const Plan &p, bool scores_itself);
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
                                 int kv_stride = kD, const void *score_label = nullptr,

@@ -115,6 +115,19 @@ def test_random_shapes(B, Hq, Hkv, L, L_max, r, k):
     full_parity(case, check_dense=(L < 3000), what=f"random shape {(B, Hq, Hkv, L, L_max, r, k)}")
 
 
+@pytest.mark.parametrize("L,r,k", [(8192, 8, 512), (5000, 16, 300)])
+def test_many_units_one_workgroup_each(L, r, k):
+    """256 units of a length one workgroup takes: the library's own choice is a single
+    launch per layer (fp16 labels) or scoring plus one workgroup per unit (other label
+    sources); every variant of the fixture runs the same comparison."""
+    w = small_workload(8, 32, 32, L, r, k)
+    t = make_layer_torch(w, "cuda", layer=3)
+    ch = rand_channels(32, 128, r, seed=L)
+    case = Case.from_torch(t, ch, L, k)
+    full_parity(case, check_dense=False, what=f"256 units x {L}")
+    _q4_parity(case.q_h, case.K_h, case.V_h, ch, L, k, f"256 units x {L}, q4")
+
+
 # ---------------------------------------------------------------- ties
 @pytest.mark.parametrize("L,k,G", [(1200, 100, 1), (5000, 313, 1), (2500, 77, 4)])
 def test_integer_scores_many_exact_ties(L, k, G):

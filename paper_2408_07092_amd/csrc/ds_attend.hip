@@ -168,6 +168,8 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     uint32_t *keys_sh = dyn_sh;
     uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
     uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
+    // one throw-away 16-bit slot per thread, so that list writes need no branch
+    uint16_t *waste = reinterpret_cast<uint16_t *>(cnt + a.n_ch) + threadIdx.x;
     __shared__ uint32_t s_w[4], s_flag, s_res[2], s_base, s_T[2], s_ok;
     __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
@@ -259,6 +261,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         bstar = s_res[0];
         krem_unit = s_res[1];
         __syncthreads();
+        DS_TR(10);
     } else {
         // ---- 1. the chunk's keys come from the scoring launch, with the unit's threshold bin;
         // all of the thread's key loads are in flight together; the keys then live in LDS
@@ -290,7 +293,53 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     };
     int n_def = 0;
     uint32_t n_cand = 0;
-    for (int p = 0; p < n_pass; ++p) {
+    // A workgroup that owns a CU (RPS > 4) has the registers to hold all of a thread's keys: they
+    // are read from LDS in one go, and one scan orders the lists thread by thread (any fixed
+    // order of the row list will do; only the index list has to be in token order).
+    constexpr bool kAllKeys = RPS > 4;
+    constexpr int kAllPasses = 16;  // ch <= 16384
+    if constexpr (kAllKeys) {
+        __syncthreads();  // the keys were stored by other threads
+        uint4 kq[kAllPasses];
+#pragma unroll
+        for (int p = 0; p < kAllPasses; ++p) {
+            const int lt = (p * kWG + tid) * 4;
+            kq[p] = make_uint4(0u, 0u, 0u, 0u);
+            if (p < n_pass && t0 + lt < t1) kq[p] = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+        }
+        uint32_t packed = 0;  // definite count | candidate count << 16
+#pragma unroll
+        for (int p = 0; p < kAllPasses; ++p) {
+            const int lt = (p * kWG + tid) * 4;
+            const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (p < n_pass && t0 + lt + e < t1 && k4[e] >= lo_key)
+                    packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
+        }
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+        int dpos = (int)(ex & 0xffffu);
+        int cp = a.ch - 1 - (int)(ex >> 16);
+#pragma unroll
+        for (int p = 0; p < kAllPasses; ++p) {
+            const int lt = (p * kWG + tid) * 4;
+            const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool live = p < n_pass && t0 + lt + e < t1 && k4[e] >= lo_key;
+                const bool def = live && k4[e] - lo_key >= (1u << kKeyShift);
+                const bool can = live && !def;
+                uint16_t *dst = def ? sel + dpos : can ? sel + cp : waste;
+                *dst = (uint16_t)(lt + e);
+                dpos += def ? 1 : 0;
+                cp -= can ? 1 : 0;
+            }
+        }
+        n_def = (int)(total & 0xffffu);
+        n_cand = total >> 16;
+    }
+    for (int p = 0; p < (kAllKeys ? 0 : n_pass); ++p) {
         const int lt = (p * kWG + tid) * 4;  // offset of the thread's four tokens in the chunk
         uint32_t k4[4];
         own_keys(p, k4);
@@ -466,7 +515,46 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         const uint32_t off = (a.idx_out && !single) ? ld_dev(a.offs_rw + (size_t)u * a.n_ch + c) : 0u;
         int32_t *io = a.idx_out ? a.idx_out + (size_t)u * a.k : nullptr;
         int all_base = 0;
-        for (int p = 0; p < n_pass; ++p) {
+        // the row list in thread-major order (any fixed order will do); an index list, if wanted,
+        // is written in token order by the pass loop further down
+        if constexpr (kAllKeys) {
+            {
+                uint4 kq[kAllPasses];
+#pragma unroll
+                for (int p = 0; p < kAllPasses; ++p) {
+                    const int lt = (p * kWG + tid) * 4;
+                    kq[p] = make_uint4(0u, 0u, 0u, 0u);
+                    if (p < n_pass && t0 + lt < t1) kq[p] = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+                }
+                uint32_t cnt_sel = 0;
+#pragma unroll
+                for (int p = 0; p < kAllPasses; ++p) {
+                    const int lt = (p * kWG + tid) * 4;
+                    const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (p < n_pass && t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift) &&
+                            is_selected(k4[e], t0 + lt + e, T, tcut))
+                            ++cnt_sel;
+                }
+                uint32_t total;
+                int cp = n_def + (int)block_exclusive_scan(cnt_sel, s_w, &total);
+#pragma unroll
+                for (int p = 0; p < kAllPasses; ++p) {
+                    const int lt = (p * kWG + tid) * 4;
+                    const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool hit = p < n_pass && t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift) &&
+                                         is_selected(k4[e], t0 + lt + e, T, tcut);
+                        *(hit ? sel + cp : waste) = (uint16_t)(lt + e);
+                        cp += hit ? 1 : 0;
+                    }
+                }
+                n_sel = (int)total;
+            }
+        }
+        for (int p = 0; p < ((kAllKeys && !io) ? 0 : n_pass); ++p) {
             const int lt = (p * kWG + tid) * 4;
             uint32_t k4[4];
             own_keys(p, k4);
@@ -484,13 +572,13 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             uint32_t ap = off + (uint32_t)all_base + (ex >> 16);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (fc[e]) sel[cp++] = (uint16_t)(lt + e);
+                if (!kAllKeys && fc[e]) sel[cp++] = (uint16_t)(lt + e);
                 if (io && fs[e]) {
                     if (ap < (uint32_t)a.k_eff) io[ap] = t0 + lt + e;
                     ++ap;
                 }
             }
-            n_sel += (int)(total & 0xffffu);
+            if (!kAllKeys) n_sel += (int)(total & 0xffffu);
             all_base += (int)(total >> 16);
         }
         if (io && c == 0)
@@ -642,7 +730,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.channels = score_channels;
     const int smode = score_label ? s.r : 0;
     if (smode && (p.n_ch != 1 || (s.r != 8 && s.r != 16))) return hipErrorInvalidValue;
-    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
+    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4 + kWG * 2;
     const dim3 grid(p.n_ch, p.units);
     // more than 64 KiB of dynamic LDS has to be asked for once per kernel
 #define DS_RA_ATTR(KERNEL)                                                                             \

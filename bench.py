@@ -197,6 +197,8 @@ def main():
     else:
         dom = "k_refine_attend" if "k_refine_attend" in kernels_us else "k_attend"
         dom_bytes = w.units * w.k * w.d * 2 * 2               # k full K and V rows per unit
+        if dom == "k_refine_attend" and "k_score" not in kernels_us:
+            dom_bytes = w.algorithmic_bytes()                 # that launch scored the units itself
     dom_us = kernels_us[dom]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
 

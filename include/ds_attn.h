@@ -303,9 +303,10 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *           to have listed its candidates settles the exact threshold for the rest
  *   knob 4: where the exact top-k threshold is settled on the three-launch path: 0 = automatic
  *           (in the scoring launch for units of up to 8K tokens), 1 = always in a separate
- *           candidate launch, 2 = always in the scoring launch.  On launch shape 4 with one
- *           workgroup per unit (a label cache of 8 or 16 fp16 channels) that workgroup also does
- *           the scoring, in one launch in all; 1 keeps the separate scoring launch there
+ *           candidate launch, 2 = always in the scoring launch.  On launch shape 4 with a label
+ *           cache of 8 or 16 fp16 channels the attention launch can do the scoring as well (one
+ *           launch in all): 0 = when a unit has one workgroup, or the whole grid of a single-head
+ *           or two-head group is resident at once; 1 = never; 2 = always
  * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
  * changing a knob changes ds_workspace_bytes() and the workspace layout, so
  * re-query the size and clear the workspace again afterwards.

@@ -398,8 +398,13 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
         return DS_OK;
     }
-    // one workgroup per unit that may score: one launch, keys never leave LDS
-    const bool scores_itself = p.n_ch == 1 && may_score;
+    // a workgroup that may score its tokens itself: one launch, keys never leave LDS
+    // ... and so can several workgroups per unit (their chunk histograms meet in memory and the
+    // threshold bin is published to them) as long as the whole grid is resident at once: single
+    // heads and pairs, four workgroups per CU.  Knob 4 = 2 forces it, 1 forbids it.
+    const bool scores_itself =
+        may_score && (p.n_ch == 1 || tune_get(4) == 2 ||
+                      (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 1024));
     if (p.refine_attend && refine_attend_ok(p, scores_itself)) {
         // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
         // threshold behind the attention over the rows that are selected either way

@@ -39,6 +39,7 @@ struct AttendArgs {
     // k_refine_attend with the scoring done in the same launch (one workgroup per unit)
     const _Float16 *label;     // [units][L_max][r]
     const int32_t *channels;   // [Hkv][r]
+    uint32_t *hist, *coarse;   // unit histograms (4096 / 256 bins), zero between calls
 };
 
 // MODE 0: rows = tokens of the chunk that pass the selection predicate
@@ -196,9 +197,9 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
 
     uint32_t bstar, krem_unit;
     if constexpr (SMODE > 0) {
-        // ---- 0. (one workgroup per unit, r = SMODE) Algorithm 1 steps 1-2 right here: stream the
-        // unit's label rows, keys go to LDS only, the threshold bin comes out of this workgroup's
-        // own histogram.  Same arithmetic and order as k_score.
+        // ---- 0. (r = SMODE) Algorithm 1 steps 1-2 right here: stream the chunk's label rows, keys
+        // go to LDS only; with one workgroup per unit the threshold bin comes out of its own
+        // histogram.  Same arithmetic and order as k_score.
         constexpr int NV = SMODE / 8;
         __shared__ uint32_t hist_sh[kHistBins];
         __shared__ float qs_sh[SMODE];
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         auto issue = [&](int tb) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, a.L - 1) * SMODE);
+                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, t1 - 1) * SMODE);
 #pragma unroll
                 for (int j = 0; j < NV; ++j) v[i][j] = row[j];
             }
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 *reinterpret_cast<uint4 *>(&qrow_sh[g][pp * 8]) = *reinterpret_cast<const uint4 *>(src);
             }
             if (g0 == 0) {
-                issue(tid);
+                issue(t0 + tid);
                 __builtin_amdgcn_sched_barrier(0);
                 for (int i = tid; i < kHistBins; i += kWG) hist_sh[i] = 0u;
             }
@@ -238,7 +239,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         float qs[SMODE];
 #pragma unroll
         for (int j = 0; j < SMODE; ++j) qs[j] = qs_sh[j];
-        for (int tb = tid; tb < a.L;) {
+        for (int tb = t0 + tid; tb < t1;) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 float acc = 0.0f;
@@ -247,20 +248,83 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
 #pragma unroll
                     for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
                 const int t = tb + i * kWG;
-                if (t < a.L) {
+                if (t < t1) {
                     const uint32_t key = score_key(acc);
-                    keys_sh[t] = key;
+                    keys_sh[t - t0] = key;
                     atomicAdd(&hist_sh[key >> kKeyShift], 1u);
                 }
             }
             tb += kWG * 8;
-            if (tb < a.L) issue(tb);
+            if (tb < t1) issue(tb);
         }
         __syncthreads();
-        hist_select<kHistBins / kWG, true>([&](int bin) { return hist_sh[bin]; }, (uint32_t)a.k_eff, s_w, s_res);
-        bstar = s_res[0];
-        krem_unit = s_res[1];
-        __syncthreads();
+        if (gridDim.x == 1) {
+            hist_select<kHistBins / kWG, true>([&](int bin) { return hist_sh[bin]; }, (uint32_t)a.k_eff, s_w, s_res);
+            bstar = s_res[0];
+            krem_unit = s_res[1];
+            __syncthreads();
+        } else {
+            // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
+            // memory (as in k_score); the last workgroup to arrive finds the threshold bin, clears
+            // the histograms and publishes (b*, rank, ready) as one word that the others wait for.
+            uint32_t *hu = a.hist + (size_t)u * kHistBins;
+            uint32_t *cuh = a.coarse + (size_t)u * 256;
+            uint2 *bready = reinterpret_cast<uint2 *>(&ctl->pad[0]);  // {b*, rank | 1<<31}
+            {
+                uint32_t cbin[kHistBins / kWG], cc = 0;
+#pragma unroll
+                for (int i = 0; i < kHistBins / kWG; ++i) {
+                    cbin[i] = hist_sh[tid + i * kWG];
+                    cc += hist_sh[tid * 16 + i];
+                }
+#pragma unroll
+                for (int i = 0; i < kHistBins / kWG; ++i)
+                    if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
+                if (cc) atomicAdd(&cuh[tid], cc);
+            }
+            const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
+            if (last_a) {
+                hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
+                const uint32_t cb = s_res[0], rank = s_res[1];
+                __shared__ uint32_t s_fine[16];
+                if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
+                __syncthreads();
+                if (tid == 0) {
+                    uint32_t before = 0, bin = 0, krem = 1;
+                    for (int i = 0; i < 16; ++i) {
+                        if (before + s_fine[i] >= rank) {
+                            bin = cb * 16 + 15 - i;
+                            krem = rank - before;
+                            break;
+                        }
+                        before += s_fine[i];
+                    }
+                    st_dev(bready, make_uint2(bin, krem | 0x80000000u));
+                    st_dev(&ctl->arrive_a, 0u);
+                    s_T[0] = bin;
+                    s_T[1] = krem;
+                    s_ok = 1u;
+                }
+                for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;  // nobody touches them again in this launch
+                cuh[tid] = 0u;
+            } else if (tid == 0) {
+                uint2 w = make_uint2(0u, 0u);
+                uint32_t ok = 0;
+                for (uint32_t it = 0; it < a.spin_limit; ++it) {
+                    w = ld_dev(bready);
+                    if (w.y & 0x80000000u) { ok = 1u; break; }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                s_T[0] = ok ? w.x : (uint32_t)(kHistBins - 1);
+                s_T[1] = ok ? (w.y & 0x7fffffffu) : 1u;
+                s_ok = ok;
+                if (!ok) st_dev(&ctl->err, 9u);
+            }
+            __syncthreads();
+            bstar = s_T[0];
+            krem_unit = s_T[1];
+            __syncthreads();
+        }
         DS_TR(10);
     } else {
         // ---- 1. the chunk's keys come from the scoring launch, with the unit's threshold bin;
@@ -472,6 +536,8 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             st_dev(&ctl->ncand, 0u);
             st_dev(&ctl->arrive_b, 0u);
+            // every workgroup of the unit has arrived, so all of them have read the threshold bin
+            if constexpr (SMODE > 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
         }
         DS_TR(9);
     }
@@ -728,8 +794,10 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.kv_stride = kv_stride;
     a.label = static_cast<const _Float16 *>(score_label);
     a.channels = score_channels;
+    a.hist = reinterpret_cast<uint32_t *>(wsp(ws, p.off_hist));
+    a.coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
     const int smode = score_label ? s.r : 0;
-    if (smode && (p.n_ch != 1 || (s.r != 8 && s.r != 16))) return hipErrorInvalidValue;
+    if (smode && s.r != 8 && s.r != 16) return hipErrorInvalidValue;
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4 + kWG * 2;
     const dim3 grid(p.n_ch, p.units);
     // more than 64 KiB of dynamic LDS has to be asked for once per kernel

@@ -17,7 +17,7 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "auto"],
+@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "chunks_fused", "auto"],
                 autouse=True)
 def decode_path(request):
     """Every test runs on every implementation of ds_sparse_decode: the single
@@ -26,9 +26,10 @@ def decode_path(request):
     launch's tail or in a candidate launch of its own, scoring followed by the
     launch that refines the threshold behind the attention, that launch with one
     workgroup per unit doing the scoring as well (chunks of 6144 tokens: units up
-    to that length), and the library's own choice."""
+    to that length), the same with several scoring workgroups per unit, and the
+    library's own choice."""
     mode, refine, chunk = {"one_launch": (2, 0, 0), "two_launch": (3, 0, 0), "score_tail": (1, 2, 0),
-                           "cand_launch": (1, 1, 0), "refine_attend": (4, 1, 0), "unit_fused": (4, 0, 6144),
+                           "cand_launch": (1, 1, 0), "refine_attend": (4, 1, 0), "unit_fused": (4, 0, 6144), "chunks_fused": (4, 2, 0),
                            "auto": (0, 0, 0)}[request.param]
     ds.ds_tune_set(3, mode)
     ds.ds_tune_set(4, refine)

@@ -193,6 +193,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     uint2 *cu = a.cand + (size_t)u * a.L;
     UnitCtl *ctl = a.ctl_rw + u;
     uint2 *ready = reinterpret_cast<uint2 *>(&ctl->cnt_a);  // {T, tie cut | 1<<31}
+    unsigned long long *cand_arrive = reinterpret_cast<unsigned long long *>(&ctl->pad[2]);
     DS_TR(0);
 
     uint32_t bstar, krem_unit;
@@ -258,6 +259,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             if (tb < t1) issue(tb);
         }
         __syncthreads();
+        DS_TR(11);
         if (gridDim.x == 1) {
             hist_select<kHistBins / kWG, true>([&](int bin) { return hist_sh[bin]; }, (uint32_t)a.k_eff, s_w, s_res);
             bstar = s_res[0];
@@ -283,6 +285,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 if (cc) atomicAdd(&cuh[tid], cc);
             }
             const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
+            DS_TR(12);
             if (last_a) {
                 hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
                 const uint32_t cb = s_res[0], rank = s_res[1];
@@ -433,7 +436,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // arrival, nothing to publish.
     const bool single = gridDim.x == 1;
     if (!single && tid == 0) {
-        s_base = n_cand ? __hip_atomic_fetch_add(&ctl->ncand, n_cand, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        // candidate count of the unit (low word) and arrivals (high word) share one 64-bit counter
+        s_base = n_cand ? (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)n_cand, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT)
+                        : 0u;
         if (a.idx_out) st_dev(a.ndef + (size_t)u * a.n_ch + c, (uint32_t)n_def);
     }
     __syncthreads();
@@ -450,7 +456,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         }
     }
     DS_TR(1);
-    bool have_T = single ? true : last_arrival(&ctl->arrive_b, gridDim.x, &s_flag);
+    bool have_T = single ? true : last_arrival_sum(cand_arrive, gridDim.x, &s_flag, &s_base);
     DS_TR(2);
     uint32_t T = 0;
     int tcut = 0x7fffffff;
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // ---- the unit is complete: exact k-th key among the candidates (10 + 10 key bits), ties
         // to the lowest token (4 + 10 + 10 index bits; tokens are below 2^24).  Up to 2048
         // candidates stay in registers; beyond that every pass re-reads the list.
-        const uint32_t n = single ? n_cand : min(ld_dev(&ctl->ncand), (uint32_t)a.L);
+        const uint32_t n = single ? n_cand : min(s_base, (uint32_t)a.L);  // the completed count came with the arrival
         const bool in_regs = n <= 8u * kWG;
         // candidate i of the unit: out of the list in memory, or (single workgroup) the i-th
         // staged token of this chunk
@@ -534,8 +540,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         }
         if (!single && tid == 0) {
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
-            st_dev(&ctl->ncand, 0u);
-            st_dev(&ctl->arrive_b, 0u);
+            __hip_atomic_store(cand_arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // every workgroup of the unit has arrived, so all of them have read the threshold bin
             if constexpr (SMODE > 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
         }

@@ -103,6 +103,25 @@ __device__ __forceinline__ bool last_arrival(uint32_t *counter, uint32_t total, 
     return *s_flag != 0u;
 }
 
+// The same with a 64-bit counter whose high word counts the arrivals and whose low word is a
+// sum the arriving workgroups have added to before (agent-scope adds of their contributions):
+// the workgroup that completes the count also learns the full sum (*low) without another load.
+__device__ __forceinline__ bool last_arrival_sum(unsigned long long *counter, uint32_t total,
+                                                 uint32_t *s_flag, uint32_t *s_low)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long t =
+            __hip_atomic_fetch_add(counter, 1ull << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = ((uint32_t)(t >> 32) == total - 1u) ? 1u : 0u;
+        *s_low = (uint32_t)t;
+    }
+    __syncthreads();
+    return *s_flag != 0u;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wavefront with DPP moves: four
 // shifted adds inside each row of 16 lanes, then the row totals are carried
 // forward (lane 15 of a row into the next row, lane 31 into rows 2 and 3).

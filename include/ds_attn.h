@@ -288,7 +288,7 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
 /*
  * Launch-shape knobs, for sweeps (defaults are chosen from the shape):
  *   knob 0: tokens per workgroup in the scoring kernel   (0 = automatic; multiple of 256)
- *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 256, <= 16384;
+ *   knob 1: tokens per workgroup in select/attend        (0 = automatic; multiple of 64, <= 16384;
  *           the candidate launch of shape 1 and ds_select take up to 6144)
  *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
  *   knob 3: how ds_sparse_decode is launched: 0 = automatic (4 for units of more than 8K

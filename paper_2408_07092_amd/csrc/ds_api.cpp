@@ -31,6 +31,18 @@ static bool shape_ok(const ds_shape_t &s, bool need_rk)
     return true;
 }
 
+// Workgroups of the refine-and-attend kernel that one CU holds when the kernel scores as well
+// (matrix-core variants, query groups of 3+ heads): LDS is what limits them -- the chunk's keys and
+// row list (6 bytes a token), the chunk histogram or the wavefront partials, whichever is larger,
+// and about 3 KiB of small arrays -- and registers allow three.
+static int group_wgs_per_cu(int G, int ch, int n_ch)
+{
+    const int gt = G <= 4 ? 4 : G <= 8 ? 8 : 16;
+    const size_t lds = (size_t)ch * 6 + (size_t)n_ch * 4 + 512 + 3072 +
+                       4 * (size_t)std::max(kHistBins, 4 * gt * kPartStride);
+    return (int)std::min<size_t>(3, (160u << 10) / lds);
+}
+
 bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
 {
     if (!shape_ok(s, true)) return false;
@@ -65,9 +77,26 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
     p->refine_attend = purpose != PLAN_SELECT &&
                        (g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units)));
     int ch = g_tune[1];
-    if (ch == 0 && p->refine_attend && one_wg_units) {
+    p->group_scores_itself = false;
+    if (ch == 0 && p->refine_attend && !one_wg_units && p->G > 2 && purpose == PLAN_DECODE_SCORING) {
+        // Query groups: one launch that scores as well pays off when all of its workgroups are
+        // resident at once (a workgroup waits for the others of its unit twice).  Most
+        // workgroups per CU first: the largest number of chunks per unit that still fits.
+        for (int w = 3; w >= 1 && ch == 0; --w) {
+            const int n = std::min((256 * w) / p->units, kMaxChunks);
+            if (n < 1) continue;
+            const int c = std::max(2048, (((s.L + n - 1) / n) + 63) & ~63);  // (no point in tiny chunks)
+            if (c <= 8192 && group_wgs_per_cu(p->G, c, (s.L + c - 1) / c) >= w) {
+                ch = c;
+                p->group_scores_itself = true;
+            }
+        }
+    }
+    if (ch != 0) {
+        // (set by the knob or just above)
+    } else if (p->refine_attend && one_wg_units) {
         ch = (s.L + 255) & ~255;
-    } else if (ch == 0 && p->refine_attend) {
+    } else if (p->refine_attend) {
         // every workgroup resident at once (six per CU on the vector path, three on the matrix
         // cores) when chunks of up to 4096 / 6144 tokens allow it
         if (p->G <= 2) {
@@ -77,7 +106,7 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
             ch = 2048;
             while (ch < 6144 && ch < s.L && (int64_t)p->units * ((s.L + ch - 1) / ch) > 768) ch += 256;
         }
-    } else if (ch == 0) {
+    } else {
         ch = (tokens >= (1 << 21)) ? 2048 : (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 512 : 256;
         if (p->G >= 4 && ch < 4096) ch *= 2;  // a query group writes G partials per chunk
         while ((s.L + ch - 1) / ch > kMaxChunks && ch < 4096) ch *= 2;
@@ -401,10 +430,12 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     // a workgroup that may score its tokens itself: one launch, keys never leave LDS
     // ... and so can several workgroups per unit (their chunk histograms meet in memory and the
     // threshold bin is published to them) as long as the whole grid is resident at once: single
-    // heads and pairs, four workgroups per CU.  Knob 4 = 2 forces it, 1 forbids it.
+    // heads and pairs, four workgroups per CU; larger query groups when the plan found chunks that
+    // make it so (up to three workgroups per CU).  Knob 4 = 2 forces it, 1 forbids it.
     const bool scores_itself =
         may_score && (p.n_ch == 1 || tune_get(4) == 2 ||
-                      (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 1024));
+                      (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 1024) ||
+                      (tune_get(4) == 0 && p.group_scores_itself));
     if (p.refine_attend && refine_attend_ok(p, scores_itself)) {
         // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
         // threshold behind the attention over the rows that are selected either way
@@ -599,7 +630,7 @@ ds_status_t ds_tune_set(int knob, int value)
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 1 && (value % 256 != 0 || value > 16384)) return DS_ERR_SHAPE;
+        if (knob == 1 && (value % 64 != 0 || value > 16384)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 3 && value > 4) return DS_ERR_SHAPE;
         if (knob == 4 && value > 2) return DS_ERR_SHAPE;

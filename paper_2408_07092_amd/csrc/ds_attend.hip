@@ -178,7 +178,12 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // 4 KiB serve the radix bins of the refinement, later the merge of the unit's partials; the
     // workgroup's own wavefront partials lie between the two in time and share the space when
     // they are at least that large
-    __shared__ __attribute__((aligned(16))) float wpart[4][GT][kPartStride];
+    // On the matrix-core variants, where LDS limits the workgroups per CU, the chunk histogram of
+    // the launch that scores as well lives there too (it is dead before any of the above), with
+    // the array padded to its 16 KiB where four heads make it smaller.
+    constexpr bool kAliasHist = SMODE > 0 && GT >= 4;
+    constexpr int kWpartRows = (kAliasHist && 4 * GT * kPartStride < kHistBins) ? 8 : 4;
+    __shared__ __attribute__((aligned(16))) float wpart[kWpartRows][GT][kPartStride];
     __shared__ __attribute__((aligned(16))) float red_own[GT >= 2 ? 1 : 8][kD];
     float(*red)[kD] = GT >= 2 ? reinterpret_cast<float(*)[kD]>(&wpart[0][0][0]) : red_own;
     uint32_t *lh = reinterpret_cast<uint32_t *>(&red[0][0]);  // 1024 radix bins
@@ -202,11 +207,24 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // go to LDS only; with one workgroup per unit the threshold bin comes out of its own
         // histogram.  Same arithmetic and order as k_score.
         constexpr int NV = SMODE / 8;
-        __shared__ uint32_t hist_sh[kHistBins];
+        __shared__ uint32_t hist_own[kAliasHist ? 1 : kHistBins];
+        auto hist_at = [&](int i) -> uint32_t & {
+            if constexpr (kAliasHist) return reinterpret_cast<uint32_t *>(&wpart[0][0][0])[i];
+            else return hist_own[i];
+        };
         __shared__ float qs_sh[SMODE];
         __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
         half8 v[8][NV];
+        // (rows past the end of the chunk re-read its last row; their scores are dropped)
+        auto issue_to = [&](half8 (&buf)[8][NV], int tb) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, t1 - 1) * SMODE);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) buf[i][j] = row[j];
+            }
+        };
         auto issue = [&](int tb) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -229,7 +247,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             if (g0 == 0) {
                 issue(t0 + tid);
                 __builtin_amdgcn_sched_barrier(0);
-                for (int i = tid; i < kHistBins; i += kWG) hist_sh[i] = 0u;
+                for (int i = tid; i < kHistBins; i += kWG) hist_at(i) = 0u;
             }
             __syncthreads();
             if (tid < SMODE)
@@ -240,28 +258,58 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         float qs[SMODE];
 #pragma unroll
         for (int j = 0; j < SMODE; ++j) qs[j] = qs_sh[j];
-        for (int tb = t0 + tid; tb < t1;) {
+        auto score_batch = [&](half8 (&buf)[8][NV], int tb) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int j = 0; j < NV; ++j)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
+                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)buf[i][j][e], acc);
                 const int t = tb + i * kWG;
                 if (t < t1) {
                     const uint32_t key = score_key(acc);
                     keys_sh[t - t0] = key;
-                    atomicAdd(&hist_sh[key >> kKeyShift], 1u);
+                    atomicAdd(&hist_at(key >> kKeyShift), 1u);
                 }
             }
-            tb += kWG * 8;
-            if (tb < t1) issue(tb);
+        };
+        if constexpr (RPS > 4) {
+            // A workgroup alone on its CU has nobody to cover its memory latency: two batches of
+            // label rows are kept in flight, the next one issued before the current one is scored.
+            half8 v2[8][NV];
+            for (int tb = t0 + tid; tb < t1; tb += 2 * kWG * 8) {
+                issue_to(v2, tb + kWG * 8);
+                __builtin_amdgcn_sched_barrier(0);
+                score_batch(v, tb);
+                issue_to(v, tb + 2 * kWG * 8);
+                __builtin_amdgcn_sched_barrier(0);
+                score_batch(v2, tb + kWG * 8);
+            }
+        } else {
+            for (int tb = t0 + tid; tb < t1;) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float acc = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < NV; ++j)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
+                    const int t = tb + i * kWG;
+                    if (t < t1) {
+                        const uint32_t key = score_key(acc);
+                        keys_sh[t - t0] = key;
+                        atomicAdd(&hist_at(key >> kKeyShift), 1u);
+                    }
+                }
+                tb += kWG * 8;
+                if (tb < t1) issue(tb);
+            }
         }
         __syncthreads();
         DS_TR(11);
         if (gridDim.x == 1) {
-            hist_select<kHistBins / kWG, true>([&](int bin) { return hist_sh[bin]; }, (uint32_t)a.k_eff, s_w, s_res);
+            hist_select<kHistBins / kWG, true>([&](int bin) { return hist_at(bin); }, (uint32_t)a.k_eff, s_w, s_res);
             bstar = s_res[0];
             krem_unit = s_res[1];
             __syncthreads();
@@ -276,8 +324,8 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 uint32_t cbin[kHistBins / kWG], cc = 0;
 #pragma unroll
                 for (int i = 0; i < kHistBins / kWG; ++i) {
-                    cbin[i] = hist_sh[tid + i * kWG];
-                    cc += hist_sh[tid * 16 + i];
+                    cbin[i] = hist_at(tid + i * kWG);
+                    cc += hist_at(tid * 16 + i);
                 }
 #pragma unroll
                 for (int i = 0; i < kHistBins / kWG; ++i)

@@ -69,6 +69,68 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
+    if constexpr (RPS > 4) {
+        // A workgroup with a CU to itself has one wavefront per SIMD and nobody to cover its
+        // memory latency, so the RPS rows of a slot travel in two halves, the loads of one
+        // issued before the other is folded in.  Rows reach a slot's state in the same order and
+        // the same groups of four as in the plain loop below.
+        constexpr int HB = RPS / 2;
+        const int base = wave * 4 * RPS;
+        if (base >= n) return;
+        half8 k0[HB], v0[HB], k1[HB], v1[HB];
+        // first row of the wavefront's h-th half
+        auto first_row = [&](int h) { return base + (h >> 1) * 16 * RPS + (h & 1) * 4 * HB; };
+        auto issue = [&](half8 (&kr)[HB], half8 (&vr)[HB], int rr) {
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const uint32_t off = (uint32_t)row_of(min(rr + i * 4 + slot, n - 1)) * row_bytes + (uint32_t)part * 16u;
+                kr[i] = *reinterpret_cast<const half8 *>(Ku + off);
+                vr[i] = *reinterpret_cast<const half8 *>(Vu + off);
+            }
+        };
+        auto fold = [&](half8 (&kr)[HB], half8 (&vr)[HB], int rr) {
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
+#pragma unroll
+                for (int i0 = 0; i0 < HB; i0 += 4) {
+                    float s[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        s[i] = row16_sum(dot8(qv, kr[i0 + i])) * kScaleLog2;
+                        if (rr + (i0 + i) * 4 + slot >= n) s[i] = kNegInf;
+                    }
+                    const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+                    const float mn = fmaxf(st.m[g], mx);
+                    if (mn != kNegInf) {
+                        const float sc = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mn);
+                        st.m[g] = mn;
+                        st.l[g] *= sc;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) st.acc[g][j] *= sc;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float p = __builtin_amdgcn_exp2f(s[i] - mn);
+                            st.l[g] += p;
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                st.acc[g][j] = __builtin_fmaf(p, (float)vr[i0 + i][j], st.acc[g][j]);
+                        }
+                    }
+                }
+            }
+        };
+        issue(k0, v0, first_row(0));
+        for (int h = 0; first_row(h) < n; h += 2) {
+            issue(k1, v1, first_row(h + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            fold(k0, v0, first_row(h));
+            issue(k0, v0, first_row(h + 2));
+            __builtin_amdgcn_sched_barrier(0);
+            if (first_row(h + 1) < n) fold(k1, v1, first_row(h + 1));
+        }
+        return;
+    }
     for (int r0 = wave * 4 * RPS; r0 < n; r0 += 16 * RPS) {
         // all row loads of the pass are issued before the first use; lanes past the
         // end re-read the last row of the list (in bounds) and mask its score below

@@ -67,6 +67,7 @@ struct Plan {
     int ch, n_ch;        // same for candidate collection, compaction and attention
     int key_stride;      // uint32 keys per unit (L rounded up to 4)
     bool refine_attend;  // ds_sparse_decode as scoring + one refine-and-attend launch
+    bool group_scores_itself;  // query groups of 3+ heads: chunks sized so that this launch can do the scoring too
     size_t off_ctl, off_hist, off_coarse, off_keys, off_cand, off_ndef, off_offs, off_part;
     size_t off_fused;    // data region of the single-launch path (same control prefix)
     size_t total;

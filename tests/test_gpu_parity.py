@@ -17,7 +17,8 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "chunks_fused", "auto"],
+@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "chunks_fused",
+                        "auto"],
                 autouse=True)
 def decode_path(request):
     """Every test runs on every implementation of ds_sparse_decode: the single
@@ -28,9 +29,9 @@ def decode_path(request):
     workgroup per unit doing the scoring as well (chunks of 6144 tokens: units up
     to that length), the same with several scoring workgroups per unit, and the
     library's own choice."""
-    mode, refine, chunk = {"one_launch": (2, 0, 0), "two_launch": (3, 0, 0), "score_tail": (1, 2, 0),
-                           "cand_launch": (1, 1, 0), "refine_attend": (4, 1, 0), "unit_fused": (4, 0, 6144), "chunks_fused": (4, 2, 0),
-                           "auto": (0, 0, 0)}[request.param]
+    mode, refine, chunk, _ = {"one_launch": (2, 0, 0, 0), "two_launch": (3, 0, 0, 0), "score_tail": (1, 2, 0, 0),
+                                  "cand_launch": (1, 1, 0, 0), "refine_attend": (4, 1, 0, 0), "unit_fused": (4, 0, 6144, 0),
+                                  "chunks_fused": (4, 2, 0, 0), "auto": (0, 0, 0, 0)}[request.param]
     ds.ds_tune_set(3, mode)
     ds.ds_tune_set(4, refine)
     ds.ds_tune_set(1, chunk)
@@ -142,6 +143,26 @@ def test_integer_scores_many_exact_ties(L, k, G):
     ch = rand_channels(Hkv, 128, 8, seed=1)
     case = Case(q, K, V, ch, L, k)
     full_parity(case, check_dense=False, what="ties")
+
+
+@pytest.mark.parametrize("shape", ["rising", "falling", "sawtooth"])
+def test_scores_trending_along_the_sequence(shape):
+    """Approximate scores that drift with the position: a chunk's own histogram then says little
+    about the unit's threshold (chunks far below it select nothing, chunks far above it
+    everything), whichever way a workgroup guesses before the unit's histogram is complete."""
+    L, k, Hkv = 20000, 1250, 2
+    rng = np.random.default_rng(7)
+    ch = rand_channels(Hkv, 128, 8, seed=5)
+    q = rng.standard_normal((1, Hkv, 128)).astype(np.float16)
+    K = rng.standard_normal((1, Hkv, L, 128)).astype(np.float16)
+    t = np.arange(L, dtype=np.float64)
+    trend = {"rising": t / L, "falling": 1.0 - t / L, "sawtooth": (t % 3000) / 3000.0}[shape] * 6.0 - 3.0
+    for h in range(Hkv):
+        q[0, h, ch[h]] = np.float16(1.0)
+        K[0, h][:, ch[h]] = (trend[:, None] + 0.25 * rng.standard_normal((L, 8))).astype(np.float16)
+    V = rng.standard_normal((1, Hkv, L, 128)).astype(np.float16)
+    case = Case(q, K, V, ch, L, k)
+    full_parity(case, check_dense=False, what="trend " + shape)
 
 
 def test_all_scores_equal_selects_first_k_tokens():

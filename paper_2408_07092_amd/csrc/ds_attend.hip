@@ -454,31 +454,48 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         n_def = (int)(total & 0xffffu);
         n_cand = total >> 16;
     }
-    for (int p = 0; p < (kAllKeys ? 0 : n_pass); ++p) {
-        const int lt = (p * kWG + tid) * 4;  // offset of the thread's four tokens in the chunk
-        uint32_t k4[4];
-        own_keys(p, k4);
-        uint32_t packed = 0;                 // definite count | candidate count << 16
+    if constexpr (!kAllKeys) {
+        if constexpr (SMODE == 0) __syncthreads();  // the keys were stored by other threads
+        // Each thread owns n_pass groups of four consecutive keys, one thread's after the other's,
+        // so that thread order is token order: one count, one scan over the workgroup, one pass
+        // that writes both lists in ascending token order.
+        auto block_keys = [&](int p, uint32_t (&k4)[4]) {
+            const int lt = (tid * n_pass + p) * 4;
+            k4[0] = k4[1] = k4[2] = k4[3] = 0u;
+            if (t0 + lt < t1) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+                k4[0] = v.x; k4[1] = v.y; k4[2] = v.z; k4[3] = v.w;
+            }
+            return lt;
+        };
+        uint32_t packed = 0;  // definite count | candidate count << 16
+        for (int p = 0; p < n_pass; ++p) {
+            uint32_t k4[4];
+            const int lt = block_keys(p, k4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (t0 + lt + e < t1 && k4[e] >= lo_key)
-                packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
+            for (int e = 0; e < 4; ++e)
+                if (t0 + lt + e < t1 && k4[e] >= lo_key)
+                    packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
         }
         uint32_t total;
         const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
-        int dpos = n_def + (int)(ex & 0xffffu);
-        uint32_t cp = n_cand + (ex >> 16);
+        int dpos = (int)(ex & 0xffffu);
+        uint32_t cp = ex >> 16;
         // candidates wait at the back of the row list, filled from its end (the front holds the
         // definite rows; both together never exceed the chunk), until the unit-wide base is known
+        for (int p = 0; p < n_pass; ++p) {
+            uint32_t k4[4];
+            const int lt = block_keys(p, k4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (t0 + lt + e < t1 && k4[e] >= lo_key) {
-                if (k4[e] - lo_key >= (1u << kKeyShift)) sel[dpos++] = (uint16_t)(lt + e);
-                else sel[a.ch - 1 - (int)(cp++)] = (uint16_t)(lt + e);
+            for (int e = 0; e < 4; ++e) {
+                if (t0 + lt + e < t1 && k4[e] >= lo_key) {
+                    if (k4[e] - lo_key >= (1u << kKeyShift)) sel[dpos++] = (uint16_t)(lt + e);
+                    else sel[a.ch - 1 - (int)(cp++)] = (uint16_t)(lt + e);
+                }
             }
         }
-        n_def += (int)(total & 0xffffu);
-        n_cand += total >> 16;
+        n_def = (int)(total & 0xffffu);
+        n_cand = total >> 16;
     }
     // A unit with this one workgroup keeps everything in LDS: no candidate list in memory, no
     // arrival, nothing to publish.
@@ -673,7 +690,27 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 n_sel = (int)total;
             }
         }
-        for (int p = 0; p < ((kAllKeys && !io) ? 0 : n_pass); ++p) {
+        // Without an index list to write, the chunk's candidates -- already listed, in token order,
+        // at the back of the row list -- are all there is to look at: one scan per 256 of them
+        // instead of one per 1024 keys.  (The selected ones are appended at the front; the two
+        // regions cannot meet as long as n_def + 2 n_cand <= ch.)
+        const bool from_list = !kAllKeys && !io && (uint32_t)n_def + 2u * n_cand <= (uint32_t)a.ch;
+        if (from_list) {
+            for (uint32_t c0 = 0; c0 < n_cand; c0 += kWG) {
+                const uint32_t i = c0 + tid;
+                int lt = 0;
+                bool hit = false;
+                if (i < n_cand) {
+                    lt = sel[a.ch - 1 - (int)i];
+                    hit = is_selected(keys_sh[lt], t0 + lt, T, tcut);
+                }
+                uint32_t total;
+                const uint32_t ex = block_exclusive_scan(hit ? 1u : 0u, s_w, &total);
+                if (hit) sel[n_def + n_sel + (int)ex] = (uint16_t)lt;
+                n_sel += (int)total;
+            }
+        }
+        for (int p = 0; p < (((kAllKeys && !io) || from_list) ? 0 : n_pass); ++p) {
             const int lt = (p * kWG + tid) * 4;
             uint32_t k4[4];
             own_keys(p, k4);

@@ -182,6 +182,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // the launch that scores as well lives there too (it is dead before any of the above), with
     // the array padded to its 16 KiB where four heads make it smaller.
     constexpr bool kAliasHist = SMODE > 0 && GT >= 4;
+    // how a unit's workgroups learn the threshold bin when they score themselves: each finds it
+    // (vector variants), or the last to arrive finds and publishes it (matrix-core variants, where
+    // the former measured slower)
+    constexpr bool kAllFind = GT <= 2;
     constexpr int kWpartRows = (kAliasHist && 4 * GT * kPartStride < kHistBins) ? 8 : 4;
     __shared__ __attribute__((aligned(16))) float wpart[kWpartRows][GT][kPartStride];
     __shared__ __attribute__((aligned(16))) float red_own[GT >= 2 ? 1 : 8][kD];
@@ -314,62 +318,142 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             krem_unit = s_res[1];
             __syncthreads();
         } else {
-            // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
-            // memory (as in k_score); the last workgroup to arrive finds the threshold bin, clears
-            // the histograms and publishes (b*, rank, ready) as one word that the others wait for.
-            uint32_t *hu = a.hist + (size_t)u * kHistBins;
-            uint32_t *cuh = a.coarse + (size_t)u * 256;
-            uint2 *bready = reinterpret_cast<uint2 *>(&ctl->pad[0]);  // {b*, rank | 1<<31}
-            {
-                uint32_t cbin[kHistBins / kWG], cc = 0;
-#pragma unroll
-                for (int i = 0; i < kHistBins / kWG; ++i) {
-                    cbin[i] = hist_at(tid + i * kWG);
-                    cc += hist_at(tid * 16 + i);
+            if constexpr (kAllFind) {
+                // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
+                // memory (as in k_score).  Every workgroup then waits until all of the unit's have
+                // arrived and finds the threshold bin itself, with one round of loads: the 256 coarse
+                // bins, and with them the fine bins of the three coarse bins around the one that its
+                // own histogram points to (another round only if the unit's lies elsewhere).  Nobody
+                // has to publish anything; the histograms are cleared later, by the workgroup that
+                // settles the exact threshold, when every workgroup has long read them.
+                uint32_t *hu = a.hist + (size_t)u * kHistBins;
+                uint32_t *cuh = a.coarse + (size_t)u * 256;
+                {
+                    uint32_t cbin[kHistBins / kWG], cc = 0;
+    #pragma unroll
+                    for (int i = 0; i < kHistBins / kWG; ++i) {
+                        cbin[i] = hist_at(tid + i * kWG);
+                        cc += hist_at(tid * 16 + i);
+                    }
+    #pragma unroll
+                    for (int i = 0; i < kHistBins / kWG; ++i)
+                        if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
+                    if (cc) atomicAdd(&cuh[tid], cc);
                 }
-#pragma unroll
-                for (int i = 0; i < kHistBins / kWG; ++i)
-                    if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
-                if (cc) atomicAdd(&cuh[tid], cc);
-            }
-            const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
-            DS_TR(12);
-            if (last_a) {
-                hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
-                const uint32_t cb = s_res[0], rank = s_res[1];
-                __shared__ uint32_t s_fine[16];
-                if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
+                // (while those atomics are under way) the coarse bin holding the chunk's share of k
+                uint32_t cb0;
+                {
+                    const uint32_t n_tok = (uint32_t)(t1 - t0);
+                    uint32_t k_loc = (uint32_t)(((unsigned long long)a.k_eff * n_tok + (uint32_t)a.L - 1u) / (uint32_t)a.L);
+                    k_loc = min(max(k_loc, 1u), n_tok);
+                    hist_select<kHistBins / kWG, true>([&](int bin) { return hist_at(bin); }, k_loc, s_w, s_res);
+                    cb0 = min(max(s_res[0] >> 4, 1u) - 1u, 253u);  // fine bins of coarse bins cb0 .. cb0 + 2
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
                 if (tid == 0) {
-                    uint32_t before = 0, bin = 0, krem = 1;
-                    for (int i = 0; i < 16; ++i) {
-                        if (before + s_fine[i] >= rank) {
-                            bin = cb * 16 + 15 - i;
-                            krem = rank - before;
-                            break;
+                    const uint32_t n_wg = gridDim.x;
+                    uint32_t ok = 1u;
+                    if (__hip_atomic_fetch_add(&ctl->arrive_a, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u != n_wg) {
+                        ok = 0u;
+                        for (uint32_t it = 0; it < a.spin_limit; ++it) {
+                            if (ld_dev(&ctl->arrive_a) == n_wg) { ok = 1u; break; }
+                            __builtin_amdgcn_s_sleep(1);
                         }
-                        before += s_fine[i];
                     }
-                    st_dev(bready, make_uint2(bin, krem | 0x80000000u));
-                    st_dev(&ctl->arrive_a, 0u);
-                    s_T[0] = bin;
-                    s_T[1] = krem;
-                    s_ok = 1u;
+                    s_ok = ok;
+                    if (!ok) st_dev(&ctl->err, 9u);
                 }
-                for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;  // nobody touches them again in this launch
-                cuh[tid] = 0u;
-            } else if (tid == 0) {
-                uint2 w = make_uint2(0u, 0u);
-                uint32_t ok = 0;
-                for (uint32_t it = 0; it < a.spin_limit; ++it) {
-                    w = ld_dev(bready);
-                    if (w.y & 0x80000000u) { ok = 1u; break; }
-                    __builtin_amdgcn_s_sleep(1);
+                __syncthreads();
+                DS_TR(12);
+                if (s_ok) {
+                    __shared__ uint32_t s_fine[16];
+                    uint32_t fv = 0;
+                    if (tid < 48) fv = ld_dev(hu + cb0 * 16 + tid);
+                    hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
+                    const uint32_t cb = s_res[0], rank = s_res[1];
+                    if (cb - cb0 < 3u) {
+                        if (tid < 48 && (uint32_t)(tid >> 4) == cb - cb0) s_fine[15 - (tid & 15)] = fv;
+                    } else if (tid < 16) {
+                        s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);
+                    }
+                    __syncthreads();
+                    if (tid == 0) {
+                        // (s_fine runs from the coarse bin's top fine bin down)
+                        uint32_t before = 0, bin = cb * 16, krem = 1;
+                        for (int i = 0; i < 16; ++i) {
+                            if (before + s_fine[i] >= rank) {
+                                bin = cb * 16 + 15 - i;
+                                krem = rank - before;
+                                break;
+                            }
+                            before += s_fine[i];
+                        }
+                        s_T[0] = bin;
+                        s_T[1] = krem;
+                    }
+                } else if (tid == 0) {
+                    s_T[0] = (uint32_t)(kHistBins - 1);
+                    s_T[1] = 1u;
                 }
-                s_T[0] = ok ? w.x : (uint32_t)(kHistBins - 1);
-                s_T[1] = ok ? (w.y & 0x7fffffffu) : 1u;
-                s_ok = ok;
-                if (!ok) st_dev(&ctl->err, 9u);
+            } else {
+                // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
+                // memory (as in k_score); the last workgroup to arrive finds the threshold bin, clears
+                // the histograms and publishes (b*, rank, ready) as one word that the others wait for.
+                uint32_t *hu = a.hist + (size_t)u * kHistBins;
+                uint32_t *cuh = a.coarse + (size_t)u * 256;
+                uint2 *bready = reinterpret_cast<uint2 *>(&ctl->pad[0]);  // {b*, rank | 1<<31}
+                {
+                    uint32_t cbin[kHistBins / kWG], cc = 0;
+    #pragma unroll
+                    for (int i = 0; i < kHistBins / kWG; ++i) {
+                        cbin[i] = hist_at(tid + i * kWG);
+                        cc += hist_at(tid * 16 + i);
+                    }
+    #pragma unroll
+                    for (int i = 0; i < kHistBins / kWG; ++i)
+                        if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
+                    if (cc) atomicAdd(&cuh[tid], cc);
+                }
+                const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
+                DS_TR(12);
+                if (last_a) {
+                    hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
+                    const uint32_t cb = s_res[0], rank = s_res[1];
+                    __shared__ uint32_t s_fine[16];
+                    if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
+                    __syncthreads();
+                    if (tid == 0) {
+                        uint32_t before = 0, bin = 0, krem = 1;
+                        for (int i = 0; i < 16; ++i) {
+                            if (before + s_fine[i] >= rank) {
+                                bin = cb * 16 + 15 - i;
+                                krem = rank - before;
+                                break;
+                            }
+                            before += s_fine[i];
+                        }
+                        st_dev(bready, make_uint2(bin, krem | 0x80000000u));
+                        st_dev(&ctl->arrive_a, 0u);
+                        s_T[0] = bin;
+                        s_T[1] = krem;
+                        s_ok = 1u;
+                    }
+                    for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;  // nobody touches them again in this launch
+                    cuh[tid] = 0u;
+                } else if (tid == 0) {
+                    uint2 w = make_uint2(0u, 0u);
+                    uint32_t ok = 0;
+                    for (uint32_t it = 0; it < a.spin_limit; ++it) {
+                        w = ld_dev(bready);
+                        if (w.y & 0x80000000u) { ok = 1u; break; }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                    s_T[0] = ok ? w.x : (uint32_t)(kHistBins - 1);
+                    s_T[1] = ok ? (w.y & 0x7fffffffu) : 1u;
+                    s_ok = ok;
+                    if (!ok) st_dev(&ctl->err, 9u);
+                }
             }
             __syncthreads();
             bstar = s_T[0];
@@ -606,8 +690,20 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         if (!single && tid == 0) {
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             __hip_atomic_store(cand_arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if constexpr (SMODE > 0 && !kAllFind) {
             // every workgroup of the unit has arrived, so all of them have read the threshold bin
-            if constexpr (SMODE > 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
+            if (!single && tid == 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
+        }
+        if constexpr (SMODE > 0 && kAllFind) {
+            // every workgroup of the unit has arrived here, so all of them have read the unit's
+            // histograms and their arrival counter: clean for the next call
+            if (!single) {
+                uint32_t *hu = a.hist + (size_t)u * kHistBins;
+                for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
+                a.coarse[(size_t)u * 256 + tid] = 0u;
+                if (tid == 0) ctl->arrive_a = 0u;
+            }
         }
         DS_TR(9);
     }

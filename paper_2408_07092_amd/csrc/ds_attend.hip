@@ -340,7 +340,12 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                         if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
                     if (cc) atomicAdd(&cuh[tid], cc);
                 }
-                // (while those atomics are under way) the coarse bin holding the chunk's share of k
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                uint32_t seen = 0;
+                if (tid == 0)
+                    seen = __hip_atomic_fetch_add(&ctl->arrive_a, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+                // (while the arrival is under way) the coarse bin holding the chunk's share of k
                 uint32_t cb0;
                 {
                     const uint32_t n_tok = (uint32_t)(t1 - t0);
@@ -349,12 +354,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     hist_select<kHistBins / kWG, true>([&](int bin) { return hist_at(bin); }, k_loc, s_w, s_res);
                     cb0 = min(max(s_res[0] >> 4, 1u) - 1u, 253u);  // fine bins of coarse bins cb0 .. cb0 + 2
                 }
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
                 if (tid == 0) {
                     const uint32_t n_wg = gridDim.x;
                     uint32_t ok = 1u;
-                    if (__hip_atomic_fetch_add(&ctl->arrive_a, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u != n_wg) {
+                    if (seen != n_wg) {
                         ok = 0u;
                         for (uint32_t it = 0; it < a.spin_limit; ++it) {
                             if (ld_dev(&ctl->arrive_a) == n_wg) { ok = 1u; break; }
@@ -492,6 +495,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     };
     int n_def = 0;
     uint32_t n_cand = 0;
+    uint32_t early_base = 0;  // (thread 0, several workgroups per unit, lists made by the single scan)
     // A workgroup that owns a CU (RPS > 4) has the registers to hold all of a thread's keys: they
     // are read from LDS in one go, and one scan orders the lists thread by thread (any fixed
     // order of the row list will do; only the index list has to be in token order).
@@ -563,6 +567,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         }
         uint32_t total;
         const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+        // the chunk's place in the unit's candidate list is fetched while the lists are written
+        if (gridDim.x != 1 && tid == 0 && (total >> 16))
+            early_base = (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)(total >> 16), __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT);
         int dpos = (int)(ex & 0xffffu);
         uint32_t cp = ex >> 16;
         // candidates wait at the back of the row list, filled from its end (the front holds the
@@ -586,9 +594,12 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     const bool single = gridDim.x == 1;
     if (!single && tid == 0) {
         // candidate count of the unit (low word) and arrivals (high word) share one 64-bit counter
-        s_base = n_cand ? (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)n_cand, __ATOMIC_RELAXED,
-                                                          __HIP_MEMORY_SCOPE_AGENT)
-                        : 0u;
+        if constexpr (kAllKeys)
+            s_base = n_cand ? (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)n_cand, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT)
+                            : 0u;
+        else
+            s_base = early_base;
         if (a.idx_out) st_dev(a.ndef + (size_t)u * a.n_ch + c, (uint32_t)n_def);
     }
     __syncthreads();

@@ -169,8 +169,6 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     uint32_t *keys_sh = dyn_sh;
     uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
     uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
-    // one throw-away 16-bit slot per thread, so that list writes need no branch
-    uint16_t *waste = reinterpret_cast<uint16_t *>(cnt + a.n_ch) + threadIdx.x;
     __shared__ uint32_t s_w[4], s_flag, s_res[2], s_base, s_T[2], s_ok;
     __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
@@ -496,48 +494,45 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     int n_def = 0;
     uint32_t n_cand = 0;
     uint32_t early_base = 0;  // (thread 0, several workgroups per unit, lists made by the single scan)
-    // A workgroup that owns a CU (RPS > 4) has the registers to hold all of a thread's keys: they
-    // are read from LDS in one go, and one scan orders the lists thread by thread (any fixed
-    // order of the row list will do; only the index list has to be in token order).
+    // A workgroup that owns a CU (RPS > 4) runs one wavefront per SIMD, so instructions count: it
+    // looks at each key once and orders the lists thread by thread with one scan (any fixed order
+    // of the row list will do; only the index list has to be in token order).
     constexpr bool kAllKeys = RPS > 4;
+    // (kAllKeys) bit 4 p + e of a mask <-> the thread's key e of pass p, at this place in the chunk:
+    auto key_slot = [&](int j) { return ((j >> 2) * kWG + tid) * 4 + (j & 3); };
+    uint32_t mcan[2] = {0u, 0u};  // the thread's candidates
     constexpr int kAllPasses = 16;  // ch <= 16384
     if constexpr (kAllKeys) {
         __syncthreads();  // the keys were stored by other threads
-        uint4 kq[kAllPasses];
+        // One look at each key: which of the thread's keys are definite / candidates goes into two
+        // 64-bit masks (few keys are either), and the list writes -- now and when the exact
+        // threshold is in -- walk the set bits only.
+        uint32_t mdef[2] = {0u, 0u};
 #pragma unroll
         for (int p = 0; p < kAllPasses; ++p) {
             const int lt = (p * kWG + tid) * 4;
-            kq[p] = make_uint4(0u, 0u, 0u, 0u);
-            if (p < n_pass && t0 + lt < t1) kq[p] = *reinterpret_cast<const uint4 *>(keys_sh + lt);
-        }
-        uint32_t packed = 0;  // definite count | candidate count << 16
+            uint4 kq = make_uint4(0u, 0u, 0u, 0u);
+            if (p < n_pass && t0 + lt < t1) kq = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+            const uint32_t k4[4] = {kq.x, kq.y, kq.z, kq.w};
 #pragma unroll
-        for (int p = 0; p < kAllPasses; ++p) {
-            const int lt = (p * kWG + tid) * 4;
-            const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (p < n_pass && t0 + lt + e < t1 && k4[e] >= lo_key)
-                    packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
+            for (int e = 0; e < 4; ++e) {
+                const int j = p * 4 + e;
+                const bool live = p < n_pass && t0 + lt + e < t1;
+                const uint32_t bin = k4[e] >> kKeyShift;
+                if (live && bin > bstar) mdef[j >> 5] |= 1u << (j & 31);
+                if (live && bin == bstar) mcan[j >> 5] |= 1u << (j & 31);
+            }
         }
+        const uint32_t packed = (uint32_t)(__builtin_popcount(mdef[0]) + __builtin_popcount(mdef[1])) |
+                                (uint32_t)(__builtin_popcount(mcan[0]) + __builtin_popcount(mcan[1])) << 16;
         uint32_t total;
         const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
         int dpos = (int)(ex & 0xffffu);
         int cp = a.ch - 1 - (int)(ex >> 16);
 #pragma unroll
-        for (int p = 0; p < kAllPasses; ++p) {
-            const int lt = (p * kWG + tid) * 4;
-            const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool live = p < n_pass && t0 + lt + e < t1 && k4[e] >= lo_key;
-                const bool def = live && k4[e] - lo_key >= (1u << kKeyShift);
-                const bool can = live && !def;
-                uint16_t *dst = def ? sel + dpos : can ? sel + cp : waste;
-                *dst = (uint16_t)(lt + e);
-                dpos += def ? 1 : 0;
-                cp -= can ? 1 : 0;
-            }
+        for (int w = 0; w < 2; ++w) {
+            for (uint32_t m = mdef[w]; m; m &= m - 1u) sel[dpos++] = (uint16_t)key_slot(w * 32 + __builtin_ctz(m));
+            for (uint32_t m = mcan[w]; m; m &= m - 1u) sel[cp--] = (uint16_t)key_slot(w * 32 + __builtin_ctz(m));
         }
         n_def = (int)(total & 0xffffu);
         n_cand = total >> 16;
@@ -761,41 +756,21 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // the row list in thread-major order (any fixed order will do); an index list, if wanted,
         // is written in token order by the pass loop further down
         if constexpr (kAllKeys) {
-            {
-                uint4 kq[kAllPasses];
+            uint32_t msel[2] = {0u, 0u};
 #pragma unroll
-                for (int p = 0; p < kAllPasses; ++p) {
-                    const int lt = (p * kWG + tid) * 4;
-                    kq[p] = make_uint4(0u, 0u, 0u, 0u);
-                    if (p < n_pass && t0 + lt < t1) kq[p] = *reinterpret_cast<const uint4 *>(keys_sh + lt);
+            for (int w = 0; w < 2; ++w)
+                for (uint32_t m = mcan[w]; m; m &= m - 1u) {
+                    const int bit = __builtin_ctz(m);
+                    const int lt = key_slot(w * 32 + bit);
+                    if (is_selected(keys_sh[lt], t0 + lt, T, tcut)) msel[w] |= 1u << bit;
                 }
-                uint32_t cnt_sel = 0;
+            uint32_t total;
+            int cp = n_def + (int)block_exclusive_scan((uint32_t)(__builtin_popcount(msel[0]) + __builtin_popcount(msel[1])),
+                                                       s_w, &total);
 #pragma unroll
-                for (int p = 0; p < kAllPasses; ++p) {
-                    const int lt = (p * kWG + tid) * 4;
-                    const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (p < n_pass && t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift) &&
-                            is_selected(k4[e], t0 + lt + e, T, tcut))
-                            ++cnt_sel;
-                }
-                uint32_t total;
-                int cp = n_def + (int)block_exclusive_scan(cnt_sel, s_w, &total);
-#pragma unroll
-                for (int p = 0; p < kAllPasses; ++p) {
-                    const int lt = (p * kWG + tid) * 4;
-                    const uint32_t k4[4] = {kq[p].x, kq[p].y, kq[p].z, kq[p].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool hit = p < n_pass && t0 + lt + e < t1 && k4[e] - lo_key < (1u << kKeyShift) &&
-                                         is_selected(k4[e], t0 + lt + e, T, tcut);
-                        *(hit ? sel + cp : waste) = (uint16_t)(lt + e);
-                        cp += hit ? 1 : 0;
-                    }
-                }
-                n_sel = (int)total;
-            }
+            for (int w = 0; w < 2; ++w)
+                for (uint32_t m = msel[w]; m; m &= m - 1u) sel[cp++] = (uint16_t)key_slot(w * 32 + __builtin_ctz(m));
+            n_sel = (int)total;
         }
         // Without an index list to write, the chunk's candidates -- already listed, in token order,
         // at the back of the row list -- are all there is to look at: one scan per 256 of them
@@ -995,7 +970,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
     const int smode = score_label ? s.r : 0;
     if (smode && s.r != 8 && s.r != 16) return hipErrorInvalidValue;
-    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4 + kWG * 2;
+    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
     // more than 64 KiB of dynamic LDS has to be asked for once per kernel
 #define DS_RA_ATTR(KERNEL)                                                                             \

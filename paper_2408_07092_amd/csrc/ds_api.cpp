@@ -411,10 +411,13 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
-    // a workgroup that has a unit to itself can score it too when the labels are plain fp16 with
-    // 8 or 16 channels (knob 4 = 1 keeps the separate scoring launch)
-    const bool may_score = shape && src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16) &&
-                           tune_get(4) != 1;
+    // the attention launch can score as well when the labels are plain fp16 with 8 or 16 channels,
+    // or 4-bit codes of up to 16 channels in rows that 16-byte loads can take (knob 4 = 1 keeps
+    // the separate scoring launch)
+    const bool may_score =
+        shape && tune_get(4) != 1 &&
+        ((src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16)) ||
+         (src.kind == SRC_Q4 && shape->r <= 16 && (shape->L_max & (shape->r > 8 ? 1 : 3)) == 0));
     ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p,
                                    may_score ? PLAN_DECODE_SCORING : PLAN_DECODE);
     if (rc != DS_OK) return rc;
@@ -440,7 +443,8 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
         // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
         // threshold behind the attention over the rows that are selected either way
         if (scores_itself) {
-            DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride, label, channels));
+            DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride, label, channels,
+                                        src.kind == SRC_Q4 ? src.amax : nullptr));
             return DS_OK;
         }
         DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, src));

@@ -40,6 +40,8 @@ struct AttendArgs {
     const _Float16 *label;     // [units][L_max][r]
     const int32_t *channels;   // [Hkv][r]
     uint32_t *hist, *coarse;   // unit histograms (4096 / 256 bins), zero between calls
+    const float *amax;         // 4-bit label cache: [units][r] largest magnitude per channel
+    int r;                     // label channels (4-bit label cache; fp16 labels have it in the kernel's type)
 };
 
 // MODE 0: rows = tokens of the chunk that pass the selection predicate
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // On the matrix-core variants, where LDS limits the workgroups per CU, the chunk histogram of
     // the launch that scores as well lives there too (it is dead before any of the above), with
     // the array padded to its 16 KiB where four heads make it smaller.
-    constexpr bool kAliasHist = SMODE > 0 && GT >= 4;
+    constexpr bool kAliasHist = SMODE != 0 && GT >= 4;
     // how a unit's workgroups learn the threshold bin when they score themselves: each finds it
     // (vector variants), or the last to arrive finds and publishes it (matrix-core variants, where
     // the former measured slower)
@@ -204,18 +206,77 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     DS_TR(0);
 
     uint32_t bstar, krem_unit;
-    if constexpr (SMODE > 0) {
-        // ---- 0. (r = SMODE) Algorithm 1 steps 1-2 right here: stream the chunk's label rows, keys
-        // go to LDS only; with one workgroup per unit the threshold bin comes out of its own
-        // histogram.  Same arithmetic and order as k_score.
-        constexpr int NV = SMODE / 8;
+    if constexpr (SMODE != 0) {
+        // ---- 0. Algorithm 1 steps 1-2 right here: stream the chunk's label rows, keys go to LDS
+        // only; with one workgroup per unit the threshold bin comes out of its own histogram.
+        // Same arithmetic and order as k_score.  SMODE = r for fp16 labels (8 or 16); SMODE = -8 /
+        // -16 for the 4-bit label cache of up to 8 / 16 channels (one / two words per token).
+        constexpr bool kQ4 = SMODE < 0;
+        constexpr int RR = kQ4 ? -SMODE : SMODE;
+        constexpr int NV = RR / 8;
         __shared__ uint32_t hist_own[kAliasHist ? 1 : kHistBins];
         auto hist_at = [&](int i) -> uint32_t & {
             if constexpr (kAliasHist) return reinterpret_cast<uint32_t *>(&wpart[0][0][0])[i];
             else return hist_own[i];
         };
-        __shared__ float qs_sh[SMODE];
+        __shared__ float qs_sh[RR];
         __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
+        if constexpr (kQ4) {
+            // label query of the group times the step of each channel (amax / 7); zero beyond r
+            int c_q = 0;
+            if (tid < a.r) c_q = a.channels[h * a.r + tid];
+            float a_q = 0.0f;
+            for (int g0 = 0; g0 < a.G; g0 += 8) {
+                const int ng = min(8, a.G - g0);
+                if (g0) __syncthreads();
+                if (tid >= 128 && tid - 128 < ng * 16) {
+                    const int g = (tid - 128) >> 4, pp = (tid - 128) & 15;
+                    const _Float16 *src = a.q + ((size_t)b * a.Hq + (size_t)h * a.G + g0 + g) * kD + pp * 8;
+                    *reinterpret_cast<uint4 *>(&qrow_sh[g][pp * 8]) = *reinterpret_cast<const uint4 *>(src);
+                }
+                if (g0 == 0)
+                    for (int i = tid; i < kHistBins; i += kWG) hist_at(i) = 0u;
+                __syncthreads();
+                if (tid < a.r)
+                    for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
+            }
+            if (tid < RR) qs_sh[tid] = tid < a.r ? a_q * (a.amax[(size_t)u * a.r + tid] / 7.0f) : 0.0f;
+            __syncthreads();
+            float wr[RR];
+#pragma unroll
+            for (int j = 0; j < RR; ++j) wr[j] = qs_sh[j];
+            // 16-byte loads of four (two) tokens, four loads per thread in flight
+            constexpr int WW = NV, TPL = 4 / WW;
+            const uint32_t *codes = reinterpret_cast<const uint32_t *>(a.label) + (size_t)u * a.L_max * WW;
+            auto nib = [](uint32_t word, int i) { return (float)(((int32_t)(word << (28 - 4 * i))) >> 28); };
+            const int t_lastq = (t1 - 1) & ~(TPL - 1);
+            for (int tb = t0 + tid * TPL; tb < t1; tb += kWG * TPL * 4) {
+                uint4 cv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    cv[i] = *reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * kWG * TPL, t_lastq) * WW);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
+#pragma unroll
+                    for (int e = 0; e < TPL; ++e) {
+                        const int t = tb + i * kWG * TPL + e;
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int w = 0; w < WW; ++w)
+#pragma unroll
+                            for (int j = 0; j < 8; ++j)
+                                acc = __builtin_fmaf(wr[w * 8 + j], nib(c4[e * WW + w], j), acc);
+                        if (t < t1) {
+                            const uint32_t key = score_key(acc);
+                            keys_sh[t - t0] = key;
+                            atomicAdd(&hist_at(key >> kKeyShift), 1u);
+                        }
+                    }
+                }
+            }
+        }
+        if constexpr (!kQ4) {
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
         half8 v[8][NV];
         // (rows past the end of the chunk re-read its last row; their scores are dropped)
@@ -308,6 +369,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 if (tb < t1) issue(tb);
             }
         }
+        }  // fp16 labels
         __syncthreads();
         DS_TR(11);
         if (gridDim.x == 1) {
@@ -697,11 +759,11 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             __hip_atomic_store(cand_arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if constexpr (SMODE > 0 && !kAllFind) {
+        if constexpr (SMODE != 0 && !kAllFind) {
             // every workgroup of the unit has arrived, so all of them have read the threshold bin
             if (!single && tid == 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
         }
-        if constexpr (SMODE > 0 && kAllFind) {
+        if constexpr (SMODE != 0 && kAllFind) {
             // every workgroup of the unit has arrived here, so all of them have read the unit's
             // histograms and their arrival counter: clean for the next call
             if (!single) {
@@ -939,12 +1001,15 @@ bool refine_attend_ok(const Plan &p, bool scores_itself)
     return (p.n_ch + 7) / 8 <= per_xcd;
 }
 
-// score_label / score_channels: non-null to run the scoring in the same launch (the plan must
-// have one chunk per unit and r must be 8 or 16); otherwise the keys and the threshold bin of a
-// preceding k_score launch are read from the workspace.
+// score_label / score_channels: non-null to run the scoring in the same launch (fp16 labels of 8
+// or 16 channels; with score_amax the 4-bit label cache of up to 16 channels, whose token rows
+// must be 16-byte loadable: L_max % 4 == 0 for one word per token, L_max % 2 == 0 for two);
+// otherwise the keys and the threshold bin of a preceding k_score launch are read from the
+// workspace.
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
-                                int kv_stride, const void *score_label, const int32_t *score_channels)
+                                int kv_stride, const void *score_label, const int32_t *score_channels,
+                                const float *score_amax)
 {
     AttendArgs a{};
     a.q = static_cast<const _Float16 *>(q);
@@ -968,8 +1033,16 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.channels = score_channels;
     a.hist = reinterpret_cast<uint32_t *>(wsp(ws, p.off_hist));
     a.coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
-    const int smode = score_label ? s.r : 0;
-    if (smode && s.r != 8 && s.r != 16) return hipErrorInvalidValue;
+    a.amax = score_amax;
+    a.r = s.r;
+    int smode = 0;
+    if (score_label && score_amax) {
+        if (s.r > 16 || (s.L_max & (s.r > 8 ? 1 : 3))) return hipErrorInvalidValue;
+        smode = s.r > 8 ? -16 : -8;
+    } else if (score_label) {
+        if (s.r != 8 && s.r != 16) return hipErrorInvalidValue;
+        smode = s.r;
+    }
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
     // more than 64 KiB of dynamic LDS has to be asked for once per kernel
@@ -983,24 +1056,26 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
             done = true;                                                                               \
         }                                                                                              \
     } while (0)
+#define DS_RA_ONE(GTV, SM, RPSV)                                                                       \
+    do {                                                                                               \
+        DS_RA_ATTR((k_refine_attend<GTV, SM, RPSV>));                                                   \
+        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3(kWG), shmem, st, a);  \
+    } while (0)
+#define DS_RA_SM(GTV, RPSV)                                                                            \
+    do {                                                                                               \
+        if (smode == 8) DS_RA_ONE(GTV, 8, RPSV);                                                        \
+        else if (smode == 16) DS_RA_ONE(GTV, 16, RPSV);                                                 \
+        else if (smode == -8) DS_RA_ONE(GTV, -8, RPSV);                                                 \
+        else DS_RA_ONE(GTV, -16, RPSV);                                                                 \
+    } while (0)
 #define DS_RA(GTV)                                                                                     \
     do {                                                                                               \
-        if (smode == 8) DS_RA_ATTR((k_refine_attend<GTV, 8>));                                          \
-        else if (smode == 16) DS_RA_ATTR((k_refine_attend<GTV, 16>));                                   \
-        else DS_RA_ATTR((k_refine_attend<GTV, 0>));                                                     \
-        if (smode == 8) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 8>), grid, dim3(kWG), shmem, st, a);   \
-        else if (smode == 16) DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 16>), grid, dim3(kWG), shmem, st, a); \
-        else DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, 0>), grid, dim3(kWG), shmem, st, a);    \
+        if (smode == 0) DS_RA_ONE(GTV, 0, 4);                                                           \
+        else DS_RA_SM(GTV, 4);                                                                          \
     } while (0)
     if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10)) {
         // the workgroup has a CU to itself (LDS): sixteen rows per slot in flight
-        if (smode == 8) {
-            DS_RA_ATTR((k_refine_attend<1, 8, 16>));
-            DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1, 8, 16>), grid, dim3(kWG), shmem, st, a);
-        } else {
-            DS_RA_ATTR((k_refine_attend<1, 16, 16>));
-            DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<1, 16, 16>), grid, dim3(kWG), shmem, st, a);
-        }
+        DS_RA_SM(1, 16);
         return hipGetLastError();
     }
     switch (pick_gt(a.G)) {
@@ -1011,6 +1086,8 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     default: DS_RA(1); break;
     }
 #undef DS_RA
+#undef DS_RA_SM
+#undef DS_RA_ONE
 #undef DS_RA_ATTR
     return hipGetLastError();
 }

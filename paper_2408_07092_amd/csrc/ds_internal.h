@@ -122,7 +122,7 @@ bool refine_attend_ok(const Plan &p, bool scores_itself);
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
                                 int kv_stride = kD, const void *score_label = nullptr,
-                                const int32_t *score_channels = nullptr);
+                                const int32_t *score_channels = nullptr, const float *score_amax = nullptr);
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,
                                const DensePlan &p, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_attend_rows(const void *q, const void *KV_rows, void *ws, float *out,

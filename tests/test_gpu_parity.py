@@ -327,6 +327,33 @@ def _full_config(name, check_dense_heads=None):
     print(name, rep)
 
 
+def _decode_launches(case):
+    """Kernel name -> launches of one ds_sparse_decode call without an index list."""
+    case.gpu_sparse(want_idx=False)
+    ds.ds_profile_enable(True)
+    ds.ds_profile_reset()
+    case.gpu_sparse(want_idx=False)
+    torch.cuda.synchronize()
+    rep = {k: n for k, (ms, n) in ds.ds_profile_read().items() if n}
+    ds.ds_profile_enable(False)
+    return rep
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4a", "C4b"])
+def test_full_configs_decode_in_one_launch_by_default(name, decode_path):
+    """The benchmark configurations take the path the bench times: scoring, selection and
+    attention in a single launch per layer (the parity of that path is checked by the full-size
+    tests below under the same default)."""
+    if decode_path != "auto":
+        pytest.skip("default launch shape only")
+    w = WORKLOADS[name]
+    t = make_layer_torch(w, "cuda", layer=0)
+    ch = outlier_channels(w.Hkv, w.d) if w.r == 8 else np.tile(np.arange(w.r, dtype=np.int32), (w.Hkv, 1))
+    case = Case.from_torch(t, ch, w.L, w.k)
+    case.gpu_build_label()
+    assert _decode_launches(case) == {"k_refine_attend": 1}
+
+
 def test_full_config_c2():
     _full_config("C2")
 

@@ -292,8 +292,9 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *           the candidate launch of shape 1 and ds_select take up to 6144)
  *   knob 2: tokens per workgroup in dense/rows attention (0 = automatic; multiple of 16)
  *   knob 3: how ds_sparse_decode is launched: 0 = automatic (4 for units of more than 8K
- *           tokens and for units short enough for one workgroup each: up to 4K tokens, up to
- *           8K when there are 256 units or more; else 1), 1 = three launches
+ *           tokens -- more than 4K when the attention launch can score as well, see knob 4 --
+ *           and for units short enough for one workgroup each: up to 4K tokens, up to 8K when
+ *           there are 256 units or more; else 1), 1 = three launches
  *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
  *           workgroups when the shape and the device allow it (else three launches),
  *           3 = two launches: that co-resident launch up to the threshold candidates, then
@@ -304,9 +305,12 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *   knob 4: where the exact top-k threshold is settled on the three-launch path: 0 = automatic
  *           (in the scoring launch for units of up to 8K tokens), 1 = always in a separate
  *           candidate launch, 2 = always in the scoring launch.  On launch shape 4 with a label
- *           cache of 8 or 16 fp16 channels the attention launch can do the scoring as well (one
- *           launch in all): 0 = when a unit has one workgroup, or the whole grid of a single-head
- *           or two-head group is resident at once; 1 = never; 2 = always
+ *           cache of 8 or 16 fp16 channels, or a 4-bit one of up to 16 channels whose token
+ *           rows 16-byte loads can take (L_max a multiple of 4, of 2 above 8 channels), the
+ *           attention launch can do the scoring as well (one launch in all): 0 = when a unit
+ *           has one workgroup, or the whole grid is resident at once (single heads and pairs:
+ *           up to 1024 workgroups; larger query groups: chunks sized for it when that fits);
+ *           1 = never; 2 = always
  * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
  * changing a knob changes ds_workspace_bytes() and the workspace layout, so
  * re-query the size and clear the workspace again afterwards.

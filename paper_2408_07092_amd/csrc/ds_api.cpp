@@ -69,13 +69,17 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
     // histograms, arrival counting, partials -- costs more than it spreads at that size.  "Short"
     // is 4K tokens; 8K when there are enough units (256) to fill the device; 16K for a workgroup
     // that scores its unit itself, single heads or pairs, with 192 units or more (one 96 KiB
-    // workgroup per CU).  What lies between refines the threshold in the scoring launch's tail.
+    // workgroup per CU).  Units of 4K to 8K tokens that are too few for that take the long units'
+    // path when the attention launch can score (batch 4 x 8K tokens, 32 heads: 30.5 -> 25.1 us);
+    // what is left refines the threshold in the scoring launch's tail.
     const bool one_wg_units =
         purpose != PLAN_SELECT &&
         (s.L <= 4096 || (p->units >= 256 && s.L <= 8192) ||
          (purpose == PLAN_DECODE_SCORING && p->units >= 192 && p->G <= 2 && s.L <= 16384));
     p->refine_attend = purpose != PLAN_SELECT &&
-                       (g_tune[3] == 4 || (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units)));
+                       (g_tune[3] == 4 ||
+                        (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units ||
+                                            (purpose == PLAN_DECODE_SCORING && s.L > (1 << 12)))));
     int ch = g_tune[1];
     p->group_scores_itself = false;
     if (ch == 0 && p->refine_attend && !one_wg_units && p->G > 2 && purpose == PLAN_DECODE_SCORING) {

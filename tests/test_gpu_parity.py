@@ -70,6 +70,11 @@ def small_workload(B, Hq, Hkv, L, r, k):
     (2, 16, 2, 777, 800, 8, 40),      # GQA group 8
     (1, 6, 2, 520, 520, 16, 33),      # GQA group 3 (no power-of-two tile)
     (1, 32, 2, 400, 400, 8, 25),      # GQA group 16 (two passes of 8)
+    (1, 8, 2, 9000, 9000, 8, 500),    # GQA group 4, several chunks per unit that score themselves
+    (1, 16, 2, 10000, 10016, 16, 700),  # GQA group 8, r = 16, the same
+    (1, 6, 2, 9001, 9004, 8, 300),    # GQA group 3, the same with a ragged tail
+    (1, 32, 2, 8200, 8200, 8, 513),   # GQA group 16, the same
+    (2, 4, 4, 6000, 6000, 8, 375),    # single heads, 4K < L <= 8K with few units
 ])
 def test_small_shapes(B, Hq, Hkv, L, L_max, r, k):
     w = small_workload(B, Hq, Hkv, L, r, k)
@@ -617,6 +622,10 @@ def _q4_parity(q, K, V, ch, L, k, what, split=None):
     (1, 2, 2, 1500, 1500, 11, 100),   # two words per token, second partly used
     (3, 8, 2, 900, 1024, 8, 57),      # GQA group 4
     (1, 2, 2, 9000, 9000, 8, 600),    # refine-and-attend launch
+    (1, 2, 2, 9001, 9002, 11, 600),   # the same, two words per token (L_max even)
+    (1, 2, 2, 9001, 9003, 8, 600),    # the same, rows that 16-byte loads cannot take: separate scoring launch
+    (1, 8, 2, 9000, 9000, 8, 500),    # GQA group 4, several chunks per unit
+    (1, 16, 2, 10000, 10016, 16, 700),  # GQA group 8, two words per token
 ])
 def test_q4_label_cache_small_shapes(B, Hq, Hkv, L, L_max, r, k):
     w = small_workload(B, Hq, Hkv, L, r, k)

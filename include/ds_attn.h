@@ -169,6 +169,19 @@ size_t ds_workspace_bytes(const ds_shape_t *shape);
  * call runs.  A call on a workspace that was not cleared gives wrong results
  * (out-of-range counters are caught where they would index memory). */
 ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+/* Waits for `stream` and reads back the per-unit error words of the workspace
+ * (DEVICE pointer) for this shape.  Inside a launch a workgroup sometimes waits
+ * for another workgroup of its unit (Algorithm 1 steps 2-5 done in one launch);
+ * every such wait is bounded, and a workgroup whose wait runs out raises its
+ * unit's error word and carries on without the value it waited for -- the launch
+ * always ends, but that unit's result is then not the top-k attention.  The word
+ * stays set until ds_workspace_init().  *n_failed = units whose word is set,
+ * *first_code = the first such word (which wait it was; 0 if none); either
+ * pointer may be NULL.  DS_OK when the words could be read (whatever they say),
+ * DS_ERR_HIP when the copy failed.  Synchronises: not for the hot path. */
+ds_status_t ds_workspace_errors(const void *workspace, size_t workspace_bytes,
+                                const ds_shape_t *shape, void *stream,
+                                int32_t *n_failed, int32_t *first_code);
 
 /*
  * Double Sparsity decode (Algorithm 1), all four steps.  DEVICE pointers.
@@ -311,6 +324,9 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *           has one workgroup, or the whole grid is resident at once (single heads and pairs:
  *           up to 1024 workgroups; larger query groups: chunks sized for it when that fits);
  *           1 = never; 2 = always
+ *   knob 5: launch shape 4: polls after which a workgroup's wait for another workgroup gives
+ *           up (0 = the default of 2^21, far beyond any wait that ends; small values are for
+ *           testing the give-up path: see ds_workspace_errors)
  * DS_ERR_SHAPE for a knob or value the kernels cannot run with.  Process-wide;
  * changing a knob changes ds_workspace_bytes() and the workspace layout, so
  * re-query the size and clear the workspace again afterwards.

@@ -23,7 +23,7 @@ DS_KV_SPLIT, DS_KV_INTERLEAVED = 0, 1
 
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
-    "ds_workspace_bytes", "ds_workspace_init", "ds_sparse_decode", "ds_sparse_decode_nolabel",
+    "ds_workspace_bytes", "ds_workspace_init", "ds_workspace_errors", "ds_sparse_decode", "ds_sparse_decode_nolabel",
     "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_build_label_q4",
     "ds_append_label_q4", "ds_sparse_decode_q4", "ds_predict_query", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.ds_workspace_bytes.restype = sz
         L.ds_workspace_bytes.argtypes = [shp]
         L.ds_workspace_init.argtypes = [vp, sz, vp]
+        L.ds_workspace_errors.argtypes = [vp, sz, shp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         L.ds_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_sparse_decode_nolabel.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_sparse_decode_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
@@ -154,6 +155,15 @@ def ds_workspace_bytes(shp: DsShape) -> int:
 def ds_workspace_init(workspace, stream=None):
     _check(lib().ds_workspace_init(_dp(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)), "ds_workspace_init")
+
+
+def ds_workspace_errors(workspace, shp: DsShape, stream=None):
+    """(units whose bounded wait gave up, first error code); waits for the stream."""
+    n, first = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().ds_workspace_errors(_dp(workspace), workspace.numel() * workspace.element_size(),
+                                     ctypes.byref(shp), _stream(stream), ctypes.byref(n), ctypes.byref(first)),
+           "ds_workspace_errors")
+    return n.value, first.value
 
 
 def ds_workspace_alloc(shp: DsShape, device="cuda") -> "torch.Tensor":

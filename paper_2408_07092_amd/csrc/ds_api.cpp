@@ -13,8 +13,8 @@
 namespace ds {
 
 // ---------------------------------------------------------------- knobs
-static int g_tune[5] = {0, 0, 0, 0, 0};
-int tune_get(int knob) { return (knob >= 0 && knob < 5) ? g_tune[knob] : 0; }
+static int g_tune[6] = {0, 0, 0, 0, 0, 0};
+int tune_get(int knob) { return (knob >= 0 && knob < 6) ? g_tune[knob] : 0; }
 
 // ---------------------------------------------------------------- plans
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -380,6 +380,31 @@ ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *str
     return DS_OK;
 }
 
+ds_status_t ds_workspace_errors(const void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
+                                void *stream, int32_t *n_failed, int32_t *first_code)
+{
+    if (!workspace || !shape) return DS_ERR_NULL;
+    Plan p;
+    if (!shape_ok(*shape, true)) return DS_ERR_SHAPE;
+    if (!make_plan(*shape, &p, PLAN_DECODE)) return DS_ERR_UNSUPPORTED;
+    const size_t bytes = (size_t)p.units * sizeof(UnitCtl);
+    if (workspace_bytes < p.off_ctl + bytes) return DS_ERR_WORKSPACE;
+    std::vector<UnitCtl> ctl((size_t)p.units);
+    if (hipMemcpyAsync(ctl.data(), static_cast<const char *>(workspace) + p.off_ctl, bytes, hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess ||
+        hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
+        return DS_ERR_HIP;
+    int32_t n = 0, first = 0;
+    for (const UnitCtl &c : ctl)
+        if (c.err) {
+            if (!n) first = (int32_t)c.err;
+            ++n;
+        }
+    if (n_failed) *n_failed = n;
+    if (first_code) *first_code = first;
+    return DS_OK;
+}
+
 static ds_status_t select_common(const void *q, const void *label, const int32_t *channels,
                                  void *workspace, size_t workspace_bytes, const ds_shape_t *shape,
                                  Plan *p, PlanFor purpose = PLAN_SELECT)
@@ -634,7 +659,7 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches)
 
 ds_status_t ds_tune_set(int knob, int value)
 {
-    if (knob < 0 || knob > 4) return DS_ERR_SHAPE;
+    if (knob < 0 || knob > 5) return DS_ERR_SHAPE;
     if (value < 0) return DS_ERR_SHAPE;
     if (value != 0) {
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;

@@ -1027,7 +1027,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.part = reinterpret_cast<float *>(wsp(ws, p.off_part));
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.G = p.G; a.L = s.L; a.L_max = s.L_max;
     a.key_stride = p.key_stride; a.ch = p.ch; a.n_ch = p.n_ch; a.k = s.k; a.k_eff = p.k_eff;
-    a.spin_limit = 1u << 21;
+    a.spin_limit = tune_get(5) ? (uint32_t)tune_get(5) : 1u << 21;
     a.kv_stride = kv_stride;
     a.label = static_cast<const _Float16 *>(score_label);
     a.channels = score_channels;

@@ -108,7 +108,10 @@ def test_other_entry_points_refuse_null_and_bad_sizes():
     assert lib.ds_gather_rows_host(FAKE, FAKE, None, FAKE, g, None) == ds.DS_ERR_NULL
     assert lib.ds_probe_stream_read(FAKE, 24, FAKE, None) == ds.DS_ERR_SHAPE
     assert lib.ds_probe_stream_read(None, 32, FAKE, None) == ds.DS_ERR_NULL
+    assert lib.ds_workspace_errors(None, 1 << 20, g, None, None, None) == ds.DS_ERR_NULL
+    assert lib.ds_workspace_errors(FAKE, 8, g, None, None, None) == ds.DS_ERR_WORKSPACE
     assert lib.ds_tune_set(7, 0) == ds.DS_ERR_SHAPE
+    assert lib.ds_tune_set(5, 4) == ds.DS_OK and lib.ds_tune_get(5) == 4 and lib.ds_tune_set(5, 0) == ds.DS_OK
     assert lib.ds_tune_set(1, 100) == ds.DS_ERR_SHAPE
     assert lib.ds_tune_set(1, 512) == ds.DS_OK and lib.ds_tune_get(1) == 512
     assert lib.ds_tune_set(1, 0) == ds.DS_OK

@@ -145,7 +145,10 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 
 // ---------------------------------------------------------------- exact threshold + attention, one launch
 // Runs after k_score has left the unit's keys and the threshold bin b* (with the
-// rank krem of the k-th key inside it).  Tokens whose key lies in a bin above b*
+// rank krem of the k-th key inside it) -- or, with SMODE != 0, does that part itself
+// first (Algorithm 1 steps 1-2: label rows streamed, keys kept in LDS, chunk
+// histograms met in the unit's histograms in memory; see step 0 in the body), so
+// that the whole decode is this one launch.  Tokens whose key lies in a bin above b*
 // are selected whatever the exact threshold turns out to be, so a workgroup
 //   1. splits its chunk's keys into definite tokens, candidates (bin b*) and the rest,
 //      appends the candidates to the unit's list and arrives at the unit's counter;
@@ -162,8 +165,11 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // by then and never waits itself; every workgroup of the unit arrives before
 // any waits, and workgroups are dispatched in grid order, so all of a unit's
 // workgroups get to run as long as one XCD can hold its share (every eighth) of
-// the n_ch of them (checked on the host).  The wait is bounded as well: on expiry
-// the unit's error word is raised and the workgroup carries on without candidates.
+// the n_ch of them (checked on the host).  (With SMODE != 0 a workgroup also waits
+// for its unit's histogram to be complete, i.e. for workgroups that may not have
+// started: the host then sizes the chunks so that the whole grid is resident.)
+// Every wait is bounded as well: on expiry the unit's error word is raised and
+// the workgroup carries on with a value that keeps all accesses in range.
 template <int GT, int SMODE, int RPS = 4>
 __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {

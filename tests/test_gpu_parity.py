@@ -693,13 +693,15 @@ def test_waits_that_give_up_end_the_launch_and_are_reported(decode_path):
 
 
 # ---------------------------------------------------------------- determinism across processes
-@pytest.mark.parametrize("name", ["C1", "long"])
-def test_second_process_gives_identical_bytes(name):
+@pytest.mark.parametrize("name", ["C1", "long", "C3", "C4a"])
+def test_second_process_gives_identical_bytes(name, decode_path):
     """The same binary and inputs give the same output and index bytes in this process
-    (twice) and in a fresh one."""
+    (twice) and in a fresh one (the two full-size configurations: default launch shape only)."""
     import subprocess
     import sys as _sys
     from tests.determinism_child import digest
+    if name in ("C3", "C4a") and decode_path != "auto":
+        pytest.skip("full-size configurations on the default launch shape only")
     k3, k4, k1 = ds.ds_tune_get(3), ds.ds_tune_get(4), ds.ds_tune_get(1)
     here = digest(name, k3, k4, k1)
     assert digest(name, k3, k4, k1) == here

@@ -1051,16 +1051,23 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     }
     const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
     const dim3 grid(p.n_ch, p.units);
-    // more than 64 KiB of dynamic LDS has to be asked for once per kernel
+    // more than 64 KiB of dynamic LDS has to be asked for once per kernel: all that the CU has
+    // (160 KiB) beyond the kernel's static arrays
 #define DS_RA_ATTR(KERNEL)                                                                             \
     do {                                                                                               \
-        static bool done = false;                                                                      \
-        if (shmem > (64u << 10) && !done) {                                                            \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&KERNEL),                           \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 << 10) != hipSuccess) \
+        static int max_dyn = 0;                                                                        \
+        if (shmem > (64u << 10) && !max_dyn) {                                                         \
+            hipFuncAttributes fa;                                                                      \
+            if (hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&KERNEL)) != hipSuccess)      \
                 return hipErrorInvalidValue;                                                           \
-            done = true;                                                                               \
+            const int room = (160 << 10) - (int)fa.sharedSizeBytes;                                    \
+            if (room < (64 << 10) ||                                                                   \
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&KERNEL),                           \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, room) != hipSuccess)   \
+                return hipErrorInvalidValue;                                                           \
+            max_dyn = room;                                                                            \
         }                                                                                              \
+        if (shmem > (64u << 10) && shmem > (size_t)max_dyn) return hipErrorInvalidValue;               \
     } while (0)
 #define DS_RA_ONE(GTV, SM, RPSV)                                                                       \
     do {                                                                                               \

@@ -17,8 +17,8 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "chunks_fused",
-                        "auto"],
+@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "unit_fused_big",
+                        "chunks_fused", "auto"],
                 autouse=True)
 def decode_path(request):
     """Every test runs on every implementation of ds_sparse_decode: the single
@@ -27,10 +27,12 @@ def decode_path(request):
     launch's tail or in a candidate launch of its own, scoring followed by the
     launch that refines the threshold behind the attention, that launch with one
     workgroup per unit doing the scoring as well (chunks of 6144 tokens: units up
-    to that length), the same with several scoring workgroups per unit, and the
-    library's own choice."""
+    to that length; chunks of 16384 tokens: the variant of a workgroup that has a CU to
+    itself), the same with several scoring workgroups per unit, and the library's own
+    choice."""
     mode, refine, chunk, _ = {"one_launch": (2, 0, 0, 0), "two_launch": (3, 0, 0, 0), "score_tail": (1, 2, 0, 0),
                                   "cand_launch": (1, 1, 0, 0), "refine_attend": (4, 1, 0, 0), "unit_fused": (4, 0, 6144, 0),
+                                  "unit_fused_big": (4, 0, 16384, 0),
                                   "chunks_fused": (4, 2, 0, 0), "auto": (0, 0, 0, 0)}[request.param]
     ds.ds_tune_set(3, mode)
     ds.ds_tune_set(4, refine)
@@ -418,8 +420,12 @@ def test_nolabel_rejects_bad_arguments_and_matches_label_path_bytes():
     out_l, idx_l = case.gpu_sparse()
     out_n, idx_n = case.gpu_sparse_nolabel()
     assert np.array_equal(idx_l, idx_n)
-    if ds.ds_tune_get(3) not in (2, 3):        # the co-resident launches order their partial sums differently
+    # the co-resident launches order their partial sums differently, and so does the variant of
+    # a workgroup that has a CU to itself (rows reach the slots in another order)
+    if ds.ds_tune_get(3) not in (2, 3) and ds.ds_tune_get(1) <= 8192:
         assert out_l.tobytes() == out_n.tobytes()
+    else:
+        assert np.allclose(out_l, out_n, rtol=1e-4, atol=1e-5)
     out = torch.zeros((case.B, case.Hq, case.d), dtype=torch.float32, device="cuda")
     with pytest.raises(ds.DsError) as e:
         ds.ds_sparse_decode_nolabel(case.q, None, case.V, case.ch, out, None, case.ws, case.shape)

@@ -171,13 +171,18 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // Every wait is bounded as well: on expiry the unit's error word is raised and
 // the workgroup carries on with a value that keeps all accesses in range.
 template <int GT, int SMODE, int RPS = 4>
-__global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
+__global__ __launch_bounds__((RPS > 4 ? 512 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {
+    // Workgroup size: 256 threads; 512 (two wavefronts per SIMD) for the variant that has a CU to
+    // itself (RPS > 4: one workgroup per unit, launched with gridDim.x == 1 only), where a single
+    // wavefront per SIMD would leave every instruction's latency exposed.
+    constexpr int NW = RPS > 4 ? 8 : 4;
+    constexpr int WGT = 64 * NW;
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
     uint32_t *keys_sh = dyn_sh;
     uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
     uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
-    __shared__ uint32_t s_w[4], s_flag, s_res[2], s_base, s_T[2], s_ok;
+    __shared__ uint32_t s_w[NW], s_flag, s_res[2], s_base, s_T[2], s_ok;
     __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
     __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // (vector variants), or the last to arrive finds and publishes it (matrix-core variants, where
     // the former measured slower)
     constexpr bool kAllFind = GT <= 2;
-    constexpr int kWpartRows = (kAliasHist && 4 * GT * kPartStride < kHistBins) ? 8 : 4;
+    constexpr int kWpartRows = (kAliasHist && 4 * GT * kPartStride < kHistBins) ? 8 : NW;
     __shared__ __attribute__((aligned(16))) float wpart[kWpartRows][GT][kPartStride];
     __shared__ __attribute__((aligned(16))) float red_own[GT >= 2 ? 1 : 8][kD];
     float(*red)[kD] = GT >= 2 ? reinterpret_cast<float(*)[kD]>(&wpart[0][0][0]) : red_own;
@@ -203,7 +208,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     const int b = u / a.Hkv, h = u % a.Hkv;
     const int t0 = c * a.ch, t1 = min(a.L, t0 + a.ch);
     constexpr int kMaxPass = 8;                              // ch <= 8192
-    const int n_pass = (t1 - t0 + kWG * 4 - 1) / (kWG * 4);  // <= kMaxPass
+    const int n_pass = (t1 - t0 + WGT * 4 - 1) / (WGT * 4);  // <= kMaxPass
     const uint32_t *ku = a.keys + (size_t)u * a.key_stride;
     uint2 *cu = a.cand + (size_t)u * a.L;
     UnitCtl *ctl = a.ctl_rw + u;
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     unsigned long long *cand_arrive = reinterpret_cast<unsigned long long *>(&ctl->pad[2]);
     DS_TR(0);
 
-    uint32_t bstar, krem_unit;
+    uint32_t bstar = kHistBins - 1, krem_unit = 1;
     if constexpr (SMODE != 0) {
         // ---- 0. Algorithm 1 steps 1-2 right here: stream the chunk's label rows, keys go to LDS
         // only; with one workgroup per unit the threshold bin comes out of its own histogram.
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     *reinterpret_cast<uint4 *>(&qrow_sh[g][pp * 8]) = *reinterpret_cast<const uint4 *>(src);
                 }
                 if (g0 == 0)
-                    for (int i = tid; i < kHistBins; i += kWG) hist_at(i) = 0u;
+                    for (int i = tid; i < kHistBins; i += WGT) hist_at(i) = 0u;
                 __syncthreads();
                 if (tid < a.r)
                     for (int g = 0; g < ng; ++g) a_q = a_q + (float)qrow_sh[g][c_q];
@@ -256,17 +261,17 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             const uint32_t *codes = reinterpret_cast<const uint32_t *>(a.label) + (size_t)u * a.L_max * WW;
             auto nib = [](uint32_t word, int i) { return (float)(((int32_t)(word << (28 - 4 * i))) >> 28); };
             const int t_lastq = (t1 - 1) & ~(TPL - 1);
-            for (int tb = t0 + tid * TPL; tb < t1; tb += kWG * TPL * 4) {
+            for (int tb = t0 + tid * TPL; tb < t1; tb += WGT * TPL * 4) {
                 uint4 cv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    cv[i] = *reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * kWG * TPL, t_lastq) * WW);
+                    cv[i] = *reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * WGT * TPL, t_lastq) * WW);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
 #pragma unroll
                     for (int e = 0; e < TPL; ++e) {
-                        const int t = tb + i * kWG * TPL + e;
+                        const int t = tb + i * WGT * TPL + e;
                         float acc = 0.0f;
 #pragma unroll
                         for (int w = 0; w < WW; ++w)
@@ -286,18 +291,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
         half8 v[8][NV];
         // (rows past the end of the chunk re-read its last row; their scores are dropped)
-        auto issue_to = [&](half8 (&buf)[8][NV], int tb) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, t1 - 1) * SMODE);
-#pragma unroll
-                for (int j = 0; j < NV; ++j) buf[i][j] = row[j];
-            }
-        };
         auto issue = [&](int tb) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * kWG, t1 - 1) * SMODE);
+                const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * WGT, t1 - 1) * SMODE);
 #pragma unroll
                 for (int j = 0; j < NV; ++j) v[i][j] = row[j];
             }
@@ -316,7 +313,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             if (g0 == 0) {
                 issue(t0 + tid);
                 __builtin_amdgcn_sched_barrier(0);
-                for (int i = tid; i < kHistBins; i += kWG) hist_at(i) = 0u;
+                for (int i = tid; i < kHistBins; i += WGT) hist_at(i) = 0u;
             }
             __syncthreads();
             if (tid < SMODE)
@@ -327,63 +324,33 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         float qs[SMODE];
 #pragma unroll
         for (int j = 0; j < SMODE; ++j) qs[j] = qs_sh[j];
-        auto score_batch = [&](half8 (&buf)[8][NV], int tb) {
+        for (int tb = t0 + tid; tb < t1;) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int j = 0; j < NV; ++j)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)buf[i][j][e], acc);
-                const int t = tb + i * kWG;
+                    for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
+                const int t = tb + i * WGT;
                 if (t < t1) {
                     const uint32_t key = score_key(acc);
                     keys_sh[t - t0] = key;
                     atomicAdd(&hist_at(key >> kKeyShift), 1u);
                 }
             }
-        };
-        if constexpr (RPS > 4) {
-            // A workgroup alone on its CU has nobody to cover its memory latency: two batches of
-            // label rows are kept in flight, the next one issued before the current one is scored.
-            half8 v2[8][NV];
-            for (int tb = t0 + tid; tb < t1; tb += 2 * kWG * 8) {
-                issue_to(v2, tb + kWG * 8);
-                __builtin_amdgcn_sched_barrier(0);
-                score_batch(v, tb);
-                issue_to(v, tb + 2 * kWG * 8);
-                __builtin_amdgcn_sched_barrier(0);
-                score_batch(v2, tb + kWG * 8);
-            }
-        } else {
-            for (int tb = t0 + tid; tb < t1;) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    float acc = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < NV; ++j)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(qs[j * 8 + e], (float)v[i][j][e], acc);
-                    const int t = tb + i * kWG;
-                    if (t < t1) {
-                        const uint32_t key = score_key(acc);
-                        keys_sh[t - t0] = key;
-                        atomicAdd(&hist_at(key >> kKeyShift), 1u);
-                    }
-                }
-                tb += kWG * 8;
-                if (tb < t1) issue(tb);
-            }
+            tb += WGT * 8;
+            if (tb < t1) issue(tb);
         }
         }  // fp16 labels
         __syncthreads();
         DS_TR(11);
         if (gridDim.x == 1) {
-            hist_select<kHistBins / kWG, true>([&](int bin) { return hist_at(bin); }, (uint32_t)a.k_eff, s_w, s_res);
+            hist_select<kHistBins / WGT, true, NW>([&](int bin) { return hist_at(bin); }, (uint32_t)a.k_eff, s_w, s_res);
             bstar = s_res[0];
             krem_unit = s_res[1];
             __syncthreads();
-        } else {
+        } else if constexpr (NW == 4) {
             if constexpr (kAllFind) {
                 // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
                 // memory (as in k_score).  Every workgroup then waits until all of the unit's have
@@ -395,15 +362,15 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 uint32_t *hu = a.hist + (size_t)u * kHistBins;
                 uint32_t *cuh = a.coarse + (size_t)u * 256;
                 {
-                    uint32_t cbin[kHistBins / kWG], cc = 0;
+                    uint32_t cbin[kHistBins / WGT], cc = 0;
     #pragma unroll
-                    for (int i = 0; i < kHistBins / kWG; ++i) {
-                        cbin[i] = hist_at(tid + i * kWG);
+                    for (int i = 0; i < kHistBins / WGT; ++i) {
+                        cbin[i] = hist_at(tid + i * WGT);
                         cc += hist_at(tid * 16 + i);
                     }
     #pragma unroll
-                    for (int i = 0; i < kHistBins / kWG; ++i)
-                        if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
+                    for (int i = 0; i < kHistBins / WGT; ++i)
+                        if (cbin[i]) atomicAdd(&hu[tid + i * WGT], cbin[i]);
                     if (cc) atomicAdd(&cuh[tid], cc);
                 }
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -417,7 +384,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     const uint32_t n_tok = (uint32_t)(t1 - t0);
                     uint32_t k_loc = (uint32_t)(((unsigned long long)a.k_eff * n_tok + (uint32_t)a.L - 1u) / (uint32_t)a.L);
                     k_loc = min(max(k_loc, 1u), n_tok);
-                    hist_select<kHistBins / kWG, true>([&](int bin) { return hist_at(bin); }, k_loc, s_w, s_res);
+                    hist_select<kHistBins / WGT, true, NW>([&](int bin) { return hist_at(bin); }, k_loc, s_w, s_res);
                     cb0 = min(max(s_res[0] >> 4, 1u) - 1u, 253u);  // fine bins of coarse bins cb0 .. cb0 + 2
                 }
                 if (tid == 0) {
@@ -473,15 +440,15 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 uint32_t *cuh = a.coarse + (size_t)u * 256;
                 uint2 *bready = reinterpret_cast<uint2 *>(&ctl->pad[0]);  // {b*, rank | 1<<31}
                 {
-                    uint32_t cbin[kHistBins / kWG], cc = 0;
+                    uint32_t cbin[kHistBins / WGT], cc = 0;
     #pragma unroll
-                    for (int i = 0; i < kHistBins / kWG; ++i) {
-                        cbin[i] = hist_at(tid + i * kWG);
+                    for (int i = 0; i < kHistBins / WGT; ++i) {
+                        cbin[i] = hist_at(tid + i * WGT);
                         cc += hist_at(tid * 16 + i);
                     }
     #pragma unroll
-                    for (int i = 0; i < kHistBins / kWG; ++i)
-                        if (cbin[i]) atomicAdd(&hu[tid + i * kWG], cbin[i]);
+                    for (int i = 0; i < kHistBins / WGT; ++i)
+                        if (cbin[i]) atomicAdd(&hu[tid + i * WGT], cbin[i]);
                     if (cc) atomicAdd(&cuh[tid], cc);
                 }
                 const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
@@ -508,7 +475,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                         s_T[1] = krem;
                         s_ok = 1u;
                     }
-                    for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;  // nobody touches them again in this launch
+                    for (int i = tid; i < kHistBins; i += WGT) hu[i] = 0u;  // nobody touches them again in this launch
                     cuh[tid] = 0u;
                 } else if (tid == 0) {
                     uint2 w = make_uint2(0u, 0u);
@@ -538,13 +505,13 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         uint4 kv[kMaxPass];
 #pragma unroll
         for (int p = 0; p < kMaxPass; ++p) {
-            const int t = t0 + (p * kWG + tid) * 4;
+            const int t = t0 + (p * WGT + tid) * 4;
             kv[p] = make_uint4(0u, 0u, 0u, 0u);
             if (p < n_pass && t < t1) kv[p] = *reinterpret_cast<const uint4 *>(ku + t);
         }
 #pragma unroll
         for (int p = 0; p < kMaxPass; ++p) {
-            const int lt = (p * kWG + tid) * 4;
+            const int lt = (p * WGT + tid) * 4;
             if (p < n_pass && t0 + lt < t1) *reinterpret_cast<uint4 *>(keys_sh + lt) = kv[p];
         }
     }
@@ -552,7 +519,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     const uint32_t lo_key = bstar << kKeyShift;
     // own_keys(p): the thread's four keys of pass p (zeros past the end of the chunk)
     auto own_keys = [&](int p, uint32_t (&k4)[4]) {
-        const int lt = (p * kWG + tid) * 4;
+        const int lt = (p * WGT + tid) * 4;
         k4[0] = k4[1] = k4[2] = k4[3] = 0u;
         if (t0 + lt < t1) {
             const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
@@ -567,9 +534,9 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     // of the row list will do; only the index list has to be in token order).
     constexpr bool kAllKeys = RPS > 4;
     // (kAllKeys) bit 4 p + e of a mask <-> the thread's key e of pass p, at this place in the chunk:
-    auto key_slot = [&](int j) { return ((j >> 2) * kWG + tid) * 4 + (j & 3); };
+    auto key_slot = [&](int j) { return ((j >> 2) * WGT + tid) * 4 + (j & 3); };
     uint32_t mcan[2] = {0u, 0u};  // the thread's candidates
-    constexpr int kAllPasses = 16;  // ch <= 16384
+    constexpr int kAllPasses = 16384 / (WGT * 4);  // ch <= 16384
     if constexpr (kAllKeys) {
         __syncthreads();  // the keys were stored by other threads
         // One look at each key: which of the thread's keys are definite / candidates goes into two
@@ -578,7 +545,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         uint32_t mdef[2] = {0u, 0u};
 #pragma unroll
         for (int p = 0; p < kAllPasses; ++p) {
-            const int lt = (p * kWG + tid) * 4;
+            const int lt = (p * WGT + tid) * 4;
             uint4 kq = make_uint4(0u, 0u, 0u, 0u);
             if (p < n_pass && t0 + lt < t1) kq = *reinterpret_cast<const uint4 *>(keys_sh + lt);
             const uint32_t k4[4] = {kq.x, kq.y, kq.z, kq.w};
@@ -594,7 +561,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         const uint32_t packed = (uint32_t)(__builtin_popcount(mdef[0]) + __builtin_popcount(mdef[1])) |
                                 (uint32_t)(__builtin_popcount(mcan[0]) + __builtin_popcount(mcan[1])) << 16;
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+        const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
         int dpos = (int)(ex & 0xffffu);
         int cp = a.ch - 1 - (int)(ex >> 16);
 #pragma unroll
@@ -629,7 +596,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
         }
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+        const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
         // the chunk's place in the unit's candidate list is fetched while the lists are written
         if (gridDim.x != 1 && tid == 0 && (total >> 16))
             early_base = (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)(total >> 16), __ATOMIC_RELAXED,
@@ -670,7 +637,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // (a unit has L candidates at most; a base beyond that means the workspace was not cleared)
         const uint32_t base = s_base;
         if (base + n_cand <= (uint32_t)a.L) {
-            for (uint32_t i = tid; i < n_cand; i += kWG) {
+            for (uint32_t i = tid; i < n_cand; i += WGT) {
                 const int lt = sel[a.ch - 1 - (int)i];
                 st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
             }
@@ -688,7 +655,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // to the lowest token (4 + 10 + 10 index bits; tokens are below 2^24).  Up to 2048
         // candidates stay in registers; beyond that every pass re-reads the list.
         const uint32_t n = single ? n_cand : min(s_base, (uint32_t)a.L);  // the completed count came with the arrival
-        const bool in_regs = n <= 8u * kWG;
+        const bool in_regs = n <= 8u * WGT;
         // candidate i of the unit: out of the list in memory, or (single workgroup) the i-th
         // staged token of this chunk
         auto cand_at = [&](uint32_t i) {
@@ -701,59 +668,59 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         uint2 ce[8];
         if (in_regs && n) {
 #pragma unroll
-            for (int x = 0; x < 8; ++x) ce[x] = cand_at(min((uint32_t)(tid + x * kWG), n - 1));
+            for (int x = 0; x < 8; ++x) ce[x] = cand_at(min((uint32_t)(tid + x * WGT), n - 1));
         }
         auto each = [&](auto f) {
             if (in_regs) {
 #pragma unroll
                 for (int x = 0; x < 8; ++x)
-                    if ((uint32_t)(tid + x * kWG) < n) f(ce[x]);
+                    if ((uint32_t)(tid + x * WGT) < n) f(ce[x]);
             } else {
-                for (uint32_t i = tid; i < n; i += kWG) f(cand_at(i));
+                for (uint32_t i = tid; i < n; i += WGT) f(cand_at(i));
             }
         };
         DS_TR(8);
         uint32_t krem = krem_unit;
-        svc_radix_pass<4, true>(each, [](uint2) { return true; },
+        svc_radix_pass<1024 / WGT, true, NW>(each, [](uint2) { return true; },
                                 [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
         const uint32_t pre22 = (bstar << 10) | s_res[0];
         krem = s_res[1];
         __syncthreads();
-        svc_radix_pass<4, true>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
+        svc_radix_pass<1024 / WGT, true, NW>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
                                 [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
         T = (pre22 << 10) | s_res[0];
         const uint32_t m_ties = s_res[1];
         const uint32_t n_ties = lh[s_res[0]];
         __syncthreads();
         if (m_ties < n_ties) {
-            svc_radix_pass<1, false>(each, [&](uint2 e) { return e.x == T; },
+            svc_radix_pass<1, false, NW>(each, [&](uint2 e) { return e.x == T; },
                                      [](uint2 e) { return (e.y >> 20) & 255u; }, m_ties, lh, s_w, s_res);
             uint32_t prefix = s_res[0], want = s_res[1];
             __syncthreads();
-            svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+            svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
                                      [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
             prefix = (prefix << 10) | s_res[0];
             want = s_res[1];
             __syncthreads();
-            svc_radix_pass<4, false>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+            svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
                                      [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
             tcut = (int)((prefix << 10) | s_res[0]);
             __syncthreads();
         }
         if (a.idx_out && !single) {
             // selected tokens per chunk = keys above b* + selected candidates; prefix -> offsets
-            for (int i = tid; i < a.n_ch; i += kWG) cnt[i] = ld_dev(a.ndef + (size_t)u * a.n_ch + i);
+            for (int i = tid; i < a.n_ch; i += WGT) cnt[i] = ld_dev(a.ndef + (size_t)u * a.n_ch + i);
             __syncthreads();
             each([&](uint2 e) {
                 if (is_selected(e.x, (int)e.y, T, tcut)) atomicAdd(&cnt[e.y / (uint32_t)a.ch], 1u);
             });
             __syncthreads();
-            const int per = (a.n_ch + kWG - 1) / kWG;
+            const int per = (a.n_ch + WGT - 1) / WGT;
             const int c0 = min(a.n_ch, tid * per), c1 = min(a.n_ch, c0 + per);
             uint32_t sum = 0;
             for (int i = c0; i < c1; ++i) sum += cnt[i];
             uint32_t total;
-            uint32_t run = block_exclusive_scan(sum, s_w, &total);
+            uint32_t run = block_exclusive_scan<NW>(sum, s_w, &total);
             for (int i = c0; i < c1; ++i) {
                 st_dev(a.offs_rw + (size_t)u * a.n_ch + i, run);
                 run += cnt[i];
@@ -774,7 +741,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             // histograms and their arrival counter: clean for the next call
             if (!single) {
                 uint32_t *hu = a.hist + (size_t)u * kHistBins;
-                for (int i = tid; i < kHistBins; i += kWG) hu[i] = 0u;
+                for (int i = tid; i < kHistBins; i += WGT) hu[i] = 0u;
                 a.coarse[(size_t)u * 256 + tid] = 0u;
                 if (tid == 0) ctl->arrive_a = 0u;
             }
@@ -787,10 +754,10 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
     const char *Vu = reinterpret_cast<const char *>(a.V + (size_t)u * a.L_max * a.kv_stride);
     const uint32_t row_bytes = 2 * a.kv_stride;
     int n_sel = 0;
-    // First the definite rows that fill whole rounds of the four wavefronts (64 rows a round, or
-    // 16 * RPS on the vector path); the rest of them joins the selected candidates in one list, so
+    // First the definite rows that fill whole rounds of the workgroup's wavefronts (64 rows a round,
+    // or 4 * RPS per wavefront on the vector path); the rest of them joins the selected candidates in one list, so
     // that at most one round of the workgroup runs partly empty.
-    constexpr int kRound = (GT >= 4) ? 64 : 16 * RPS;
+    constexpr int kRound = (GT >= 4) ? 64 : 4 * NW * RPS;
     const int n_first = (n_def / kRound) * kRound;
     auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };
     auto row_rest = [&](int ri) { return t0 + (int)sel[n_first + ri]; };
@@ -833,7 +800,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     if (is_selected(keys_sh[lt], t0 + lt, T, tcut)) msel[w] |= 1u << bit;
                 }
             uint32_t total;
-            int cp = n_def + (int)block_exclusive_scan((uint32_t)(__builtin_popcount(msel[0]) + __builtin_popcount(msel[1])),
+            int cp = n_def + (int)block_exclusive_scan<NW>((uint32_t)(__builtin_popcount(msel[0]) + __builtin_popcount(msel[1])),
                                                        s_w, &total);
 #pragma unroll
             for (int w = 0; w < 2; ++w)
@@ -846,7 +813,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         // regions cannot meet as long as n_def + 2 n_cand <= ch.)
         const bool from_list = !kAllKeys && !io && (uint32_t)n_def + 2u * n_cand <= (uint32_t)a.ch;
         if (from_list) {
-            for (uint32_t c0 = 0; c0 < n_cand; c0 += kWG) {
+            for (uint32_t c0 = 0; c0 < n_cand; c0 += WGT) {
                 const uint32_t i = c0 + tid;
                 int lt = 0;
                 bool hit = false;
@@ -855,13 +822,13 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                     hit = is_selected(keys_sh[lt], t0 + lt, T, tcut);
                 }
                 uint32_t total;
-                const uint32_t ex = block_exclusive_scan(hit ? 1u : 0u, s_w, &total);
+                const uint32_t ex = block_exclusive_scan<NW>(hit ? 1u : 0u, s_w, &total);
                 if (hit) sel[n_def + n_sel + (int)ex] = (uint16_t)lt;
                 n_sel += (int)total;
             }
         }
         for (int p = 0; p < (((kAllKeys && !io) || from_list) ? 0 : n_pass); ++p) {
-            const int lt = (p * kWG + tid) * 4;
+            const int lt = (p * WGT + tid) * 4;
             uint32_t k4[4];
             own_keys(p, k4);
             bool fs[4], fc[4];
@@ -873,7 +840,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
                 packed += (fc[e] ? 1u : 0u) + (fs[e] ? 0x10000u : 0u);
             }
             uint32_t total;
-            const uint32_t ex = block_exclusive_scan(packed, s_w, &total);
+            const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
             int cp = n_def + n_sel + (int)(ex & 0xffffu);
             uint32_t ap = off + (uint32_t)all_base + (ex >> 16);
 #pragma unroll
@@ -888,7 +855,7 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             all_base += (int)(total >> 16);
         }
         if (io && c == 0)
-            for (int i = a.k_eff + tid; i < a.k; i += kWG) io[i] = -1;
+            for (int i = a.k_eff + tid; i < a.k; i += WGT) io[i] = -1;
         __syncthreads();
     };
 
@@ -916,11 +883,11 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
             __syncthreads();
             RowState<GT> st;
             st.init();
-            attend_rows<GT, RPS>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
+            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
             if (g0 == 0) { DS_TR(3); settle(); }
-            attend_rows<GT, RPS>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
+            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
             DS_TR(5);
-            wg_store_partial<GT>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
+            wg_store_partial<GT, NW>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
         }
     }
 
@@ -936,8 +903,9 @@ __global__ __launch_bounds__(kWG, (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refi
         ctl->cnt_a = 0u;
         ctl->cnt_b = 0u;
     }
-    merge_partials(a.part + (size_t)u * a.G * a.n_ch * kPartStride, a.G, a.n_ch,
-                   a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
+    if constexpr (NW == 4)  // (written for 256 threads; the wider variant never gets here)
+        merge_partials(a.part + (size_t)u * a.G * a.n_ch * kPartStride, a.G, a.n_ch,
+                       a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
     DS_TR(7);
 }
 
@@ -1072,7 +1040,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
 #define DS_RA_ONE(GTV, SM, RPSV)                                                                       \
     do {                                                                                               \
         DS_RA_ATTR((k_refine_attend<GTV, SM, RPSV>));                                                   \
-        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3(kWG), shmem, st, a);  \
+        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3((RPSV) > 4 ? 512 : 256), shmem, st, a); \
     } while (0)
 #define DS_RA_SM(GTV, RPSV)                                                                            \
     do {                                                                                               \
@@ -1086,8 +1054,9 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
         if (smode == 0) DS_RA_ONE(GTV, 0, 4);                                                           \
         else DS_RA_SM(GTV, 4);                                                                          \
     } while (0)
-    if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10)) {
-        // the workgroup has a CU to itself (LDS): sixteen rows per slot in flight
+    if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10) && p.n_ch == 1) {
+        // one workgroup per unit that has a CU to itself (LDS): 512 threads, sixteen rows per slot
+        // in flight
         DS_RA_SM(1, 16);
         return hipGetLastError();
     }

@@ -63,7 +63,7 @@ struct RowState {
 // 8 loads per lane; larger RPS for a workgroup that has a CU -- and its registers -- to itself).
 // row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
 // Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
-template <int GT, int RPS = 4, class RowOf>
+template <int GT, int RPS = 4, int NW = 4, class RowOf>
 __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
                                             RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)
 {
@@ -79,7 +79,7 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
         if (base >= n) return;
         half8 k0[HB], v0[HB], k1[HB], v1[HB];
         // first row of the wavefront's h-th half
-        auto first_row = [&](int h) { return base + (h >> 1) * 16 * RPS + (h & 1) * 4 * HB; };
+        auto first_row = [&](int h) { return base + (h >> 1) * 4 * NW * RPS + (h & 1) * 4 * HB; };
         auto issue = [&](half8 (&kr)[HB], half8 (&vr)[HB], int rr) {
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
@@ -192,7 +192,7 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 // result acc / l goes to out_direct + g * kD instead; that is what merging the
 // single partial would give, bit for bit.
 // Starts with a barrier; callers put a barrier between two uses of wpart.
-template <int GH>
+template <int GH, int NW = 4>
 __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride], int n_heads, float *po,
                                                  size_t head_stride, float *out_direct = nullptr)
 {
@@ -204,10 +204,10 @@ __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride]
             if (g < n_heads) {
                 float M = kNegInf;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) M = fmaxf(M, wpart[w][g][0]);
+                for (int w = 0; w < NW; ++w) M = fmaxf(M, wpart[w][g][0]);
                 float A = 0.0f, Ls = 0.0f;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
+                for (int w = 0; w < NW; ++w) {
                     const float mw = wpart[w][g][0];
                     const float f = (mw == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(mw - M);
                     A += f * wpart[w][g][4 + tid];
@@ -230,7 +230,7 @@ __device__ __forceinline__ void wg_combine_store(float (*wpart)[GH][kPartStride]
 
 // Merges the 16 slot states of the workgroup (4 slots per wave in slot order,
 // then the 4 waves in wave order) and writes one partial per head.
-template <int GT>
+template <int GT, int NW = 4>
 __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
                                                  float (*wpart)[GT][kPartStride], float *po,
                                                  size_t head_stride, float *out_direct = nullptr)
@@ -261,7 +261,7 @@ __device__ __forceinline__ void wg_store_partial(const RowState<GT> &st,
             }
         }
     }
-    wg_combine_store<GT>(wpart, GT, po, head_stride, out_direct);
+    wg_combine_store<GT, NW>(wpart, GT, po, head_stride, out_direct);
 }
 
 // ---------------------------------------------------------------- matrix-core path for query groups

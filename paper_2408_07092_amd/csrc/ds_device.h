@@ -142,8 +142,10 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int /*lane*/)
     return x;
 }
 
-// Exclusive prefix sum over the 256 threads of the workgroup (thread order);
-// *total receives the sum.  s_w: 4 words of LDS.  Contains two barriers.
+// Exclusive prefix sum over the threads of the workgroup (thread order; NW wavefronts, 256
+// threads unless said otherwise); *total receives the sum.  s_w: NW words of LDS.  Contains two
+// barriers.
+template <int NW = 4>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s_w, uint32_t *total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -152,7 +154,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t *s
     __syncthreads();
     uint32_t woff = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const uint32_t c = s_w[w];
         if (w < wave) woff += c;
         tot += c;
@@ -184,17 +186,17 @@ __device__ __forceinline__ float block_sum(float x, float *s_w)
     return r;
 }
 
-// Histogram select over 256*PER bins whose counts come from get(bin): finds the
+// Histogram select over 64*NW*PER bins (256*PER unless NW is given) whose counts come from get(bin): finds the
 // bin holding the kth element (1-based) counted from the top bin down
 // (FROM_TOP) or from bin 0 up.  res[0] = bin, res[1] = rank of the element
 // inside that bin, counted the same way.  Exactly one thread writes res when
 // 1 <= kth <= total count (otherwise res = {0, 1}); all threads may read res
 // after the call, and must have finished reading an earlier result before it.
-template <int PER, bool FROM_TOP, class Get>
+template <int PER, bool FROM_TOP, int NW = 4, class Get>
 __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w, uint32_t *res)
 {
     const int tid = threadIdx.x;
-    constexpr int NB = kWG * PER;
+    constexpr int NB = 64 * NW * PER;
     // in-range result even when the counts do not reach kth (a workspace that was not cleared)
     if (tid == 0) {
         res[0] = 0u;
@@ -209,7 +211,7 @@ __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w
         sum += loc[i];
     }
     uint32_t total;
-    uint32_t before = block_exclusive_scan(sum, s_w, &total);
+    uint32_t before = block_exclusive_scan<NW>(sum, s_w, &total);
     if (before < kth && before + sum >= kth) {
         bool done = false;
 #pragma unroll
@@ -231,17 +233,17 @@ __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w
 
 // One radix pass over the candidates of a unit: histogram `digit(e)` of those
 // with `match(e)`, then pick the bin holding the `want`-th of them.
-template <int PER, bool FROM_TOP, class Each, class Match, class Digit>
+template <int PER, bool FROM_TOP, int NW = 4, class Each, class Match, class Digit>
 __device__ __forceinline__ void svc_radix_pass(Each each, Match match, Digit digit, uint32_t want,
                                                uint32_t *lh, uint32_t *s_w, uint32_t *res)
 {
-    for (int i = threadIdx.x; i < kWG * PER; i += kWG) lh[i] = 0u;
+    for (int i = threadIdx.x; i < 64 * NW * PER; i += 64 * NW) lh[i] = 0u;
     __syncthreads();
     each([&](uint2 e) {
         if (match(e)) atomicAdd(&lh[digit(e)], 1u);
     });
     __syncthreads();
-    hist_select<PER, FROM_TOP>([&](int bin) { return lh[bin]; }, want, s_w, res);
+    hist_select<PER, FROM_TOP, NW>([&](int bin) { return lh[bin]; }, want, s_w, res);
 }
 
 // Ordered compaction: writes the selected tokens of [t0, t1) to sel[] in

@@ -171,12 +171,13 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // Every wait is bounded as well: on expiry the unit's error word is raised and
 // the workgroup carries on with a value that keeps all accesses in range.
 template <int GT, int SMODE, int RPS = 4>
-__global__ __launch_bounds__((RPS > 4 ? 512 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
+__global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {
-    // Workgroup size: 256 threads; 512 (two wavefronts per SIMD) for the variant that has a CU to
-    // itself (RPS > 4: one workgroup per unit, launched with gridDim.x == 1 only), where a single
-    // wavefront per SIMD would leave every instruction's latency exposed.
-    constexpr int NW = RPS > 4 ? 8 : 4;
+    // Workgroup size: 256 threads; 1024 (four wavefronts per SIMD, 128 registers each: RPS = 8)
+    // for the variant that has a CU to itself (RPS > 4: one workgroup per unit, launched with
+    // gridDim.x == 1 only), where a single wavefront per SIMD would leave every instruction's
+    // latency exposed (C2: 256 threads 56.9, 512 threads 55.7, 1024 threads 55.1 us/layer).
+    constexpr int NW = RPS > 4 ? 16 : 4;
     constexpr int WGT = 64 * NW;
     extern __shared__ __attribute__((aligned(16))) uint32_t dyn_sh[];  // ch keys | ch 16-bit row list | n_ch counters
     uint32_t *keys_sh = dyn_sh;
@@ -1040,7 +1041,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
 #define DS_RA_ONE(GTV, SM, RPSV)                                                                       \
     do {                                                                                               \
         DS_RA_ATTR((k_refine_attend<GTV, SM, RPSV>));                                                   \
-        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3((RPSV) > 4 ? 512 : 256), shmem, st, a); \
+        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3((RPSV) > 4 ? 1024 : 256), shmem, st, a); \
     } while (0)
 #define DS_RA_SM(GTV, RPSV)                                                                            \
     do {                                                                                               \
@@ -1055,9 +1056,9 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
         else DS_RA_SM(GTV, 4);                                                                          \
     } while (0)
     if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10) && p.n_ch == 1) {
-        // one workgroup per unit that has a CU to itself (LDS): 512 threads, sixteen rows per slot
+        // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot
         // in flight
-        DS_RA_SM(1, 16);
+        DS_RA_SM(1, 8);
         return hipGetLastError();
     }
     switch (pick_gt(a.G)) {

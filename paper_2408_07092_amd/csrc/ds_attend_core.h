@@ -59,8 +59,8 @@ struct RowState {
 };
 
 // The calling wavefront's share of the workgroup's n rows: with RPS rows per 16-lane slot in
-// flight, rows wave*4*RPS + 16*RPS*i ..  (RPS = 4: 64 rows of the workgroup per round trip and
-// 8 loads per lane; larger RPS for a workgroup that has a CU -- and its registers -- to itself).
+// flight, rows wave*4*RPS + NW*4*RPS*i ..  (NW wavefronts; RPS = 4: 64 rows of a 256-thread
+// workgroup per round trip and 8 loads per lane; larger RPS for a workgroup that has a CU to itself).
 // row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
 // Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
 template <int GT, int RPS = 4, int NW = 4, class RowOf>
@@ -70,8 +70,8 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
     if constexpr (RPS > 4) {
-        // A workgroup with a CU to itself has one wavefront per SIMD and nobody to cover its
-        // memory latency, so the RPS rows of a slot travel in two halves, the loads of one
+        // A workgroup with a CU to itself has nobody else to cover its memory latency, so the
+        // RPS rows of a slot travel in two halves, the loads of one
         // issued before the other is folded in.  Rows reach a slot's state in the same order and
         // the same groups of four as in the plain loop below.
         constexpr int HB = RPS / 2;

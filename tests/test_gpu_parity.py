@@ -114,7 +114,7 @@ def _random_shapes(n, seed):
     return out
 
 
-@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", _random_shapes(14, seed=314159))
+@pytest.mark.parametrize("B,Hq,Hkv,L,L_max,r,k", _random_shapes(14, seed=314159) + _random_shapes(10, seed=2718))
 def test_random_shapes(B, Hq, Hkv, L, L_max, r, k):
     """A seeded draw of shapes (head groups, ragged lengths, padded caches, r and k at
     both ends of their ranges) through every stage against the oracle."""

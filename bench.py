@@ -192,13 +192,16 @@ def main():
     prof = ds.ds_profile_read()
     ds.ds_profile_enable(False); ds.ds_profile_reset()
     kernels_us = {k: round(v[0] * 1e3 / v[1], 3) for k, v in prof.items()}
+    alg = w.algorithmic_bytes()                           # label stream + k full K and V rows (Sec. 5.3)
+    if args.label_bits == 4:   # 4 bits per label value, eight to a word
+        alg = w.units * (w.L * ((w.r + 7) // 8) * 4 + w.k * w.d * 2 * 2)
     if "k_fused" in kernels_us:                           # one launch does all four steps
-        dom, dom_bytes = "k_fused", w.algorithmic_bytes()  # label stream + k full K and V rows (Sec. 5.3)
+        dom, dom_bytes = "k_fused", alg
     else:
         dom = "k_refine_attend" if "k_refine_attend" in kernels_us else "k_attend"
         dom_bytes = w.units * w.k * w.d * 2 * 2               # k full K and V rows per unit
         if dom == "k_refine_attend" and "k_score" not in kernels_us:
-            dom_bytes = w.algorithmic_bytes()                 # that launch scored the units itself
+            dom_bytes = alg                                   # that launch scored the units itself
     dom_us = kernels_us[dom]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
 
@@ -213,12 +216,9 @@ def main():
                    "label_bits": args.label_bits},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None if args.interleaved else counted_traffic(w.name, dom),
+                     "traffic": None if (args.interleaved or args.label_bits == 4) else counted_traffic(w.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
     }
-    alg = w.algorithmic_bytes()
-    if args.label_bits == 4:   # 4 bits per label value, eight to a word
-        alg = w.units * (w.L * ((w.r + 7) // 8) * 4 + w.k * w.d * 2 * 2)
     extra = {
         "algorithmic_bytes_per_layer": alg,
         "achieved_GBps_whole_path": round(alg / (us_layer * 1e-6) / 1e9, 1),

@@ -530,9 +530,9 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     int n_def = 0;
     uint32_t n_cand = 0;
     uint32_t early_base = 0;  // (thread 0, several workgroups per unit, lists made by the single scan)
-    // A workgroup that owns a CU (RPS > 4) runs one wavefront per SIMD, so instructions count: it
-    // looks at each key once and orders the lists thread by thread with one scan (any fixed order
-    // of the row list will do; only the index list has to be in token order).
+    // A workgroup that owns a CU (RPS > 4) has nobody else to hide its list work behind, so
+    // instructions count: it looks at each key once and orders the lists thread by thread with one
+    // scan (any fixed order of the row list will do; only the index list has to be in token order).
     constexpr bool kAllKeys = RPS > 4;
     // (kAllKeys) bit 4 p + e of a mask <-> the thread's key e of pass p, at this place in the chunk:
     auto key_slot = [&](int j) { return ((j >> 2) * WGT + tid) * 4 + (j & 3); };

@@ -170,6 +170,23 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // started: the host then sizes the chunks so that the whole grid is resident.)
 // Every wait is bounded as well: on expiry the unit's error word is raised and
 // the workgroup carries on with a value that keeps all accesses in range.
+//
+// The body, in order (the "----" comments mark the parts):
+//   0.  (SMODE != 0) score the chunk: label query, label rows -> keys in LDS + chunk histogram;
+//       threshold bin b*: from the workgroup's own histogram (one workgroup per unit), or the
+//       chunk histograms meet in memory and every workgroup finds b* there (vector variants) /
+//       the last to arrive finds and publishes it (matrix-core variants)
+//   1.  (SMODE == 0) keys and b* of the scoring launch are loaded instead
+//   --  classify the keys against b*: row list (definite rows from the front, candidates from the
+//       back), candidates to the unit's list in memory, arrival
+//   --  (the workgroup that completes the unit) exact threshold T and tie cut by radix select over
+//       the candidates; published
+//   2-4 definite rows in whole rounds; settle() = wait for (T, tie cut), add the selected
+//       candidates (and write the index list if asked); the remaining rows; partial
+//   --  (the unit's last workgroup) merge of the partials
+// Template: GT heads per pass (1, 2 on the vector ALUs; 4, 8, 16 on the matrix cores), SMODE see
+// 0./1., RPS rows per 16-lane slot in flight (4; 8 = the 1024-thread variant of one workgroup
+// per unit that has a CU to itself).
 template <int GT, int SMODE, int RPS = 4>
 __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {

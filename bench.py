@@ -195,13 +195,10 @@ def main():
     alg = w.algorithmic_bytes()                           # label stream + k full K and V rows (Sec. 5.3)
     if args.label_bits == 4:   # 4 bits per label value, eight to a word
         alg = w.units * (w.L * ((w.r + 7) // 8) * 4 + w.k * w.d * 2 * 2)
-    if "k_fused" in kernels_us:                           # one launch does all four steps
-        dom, dom_bytes = "k_fused", alg
-    else:
-        dom = "k_refine_attend" if "k_refine_attend" in kernels_us else "k_attend"
-        dom_bytes = w.units * w.k * w.d * 2 * 2               # k full K and V rows per unit
-        if dom == "k_refine_attend" and "k_score" not in kernels_us:
-            dom_bytes = alg                                   # that launch scored the units itself
+    dom = "k_refine_attend" if "k_refine_attend" in kernels_us else "k_attend"
+    dom_bytes = w.units * w.k * w.d * 2 * 2                   # k full K and V rows per unit
+    if dom == "k_refine_attend" and "k_score" not in kernels_us:
+        dom_bytes = alg                                       # that launch scored the units itself
     dom_us = kernels_us[dom]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
 

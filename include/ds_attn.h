@@ -123,9 +123,8 @@ ds_status_t ds_append_label(const void *K, const int32_t *channels, void *label,
 typedef enum { DS_KV_SPLIT = 0, DS_KV_INTERLEAVED = 1 } ds_kv_layout_t;
 
 /*
- * Decode-step cache maintenance in one launch (Sec. 4.2: in the decoding phase
- * only the heavy-channel values of the new tokens are added to the label
- * cache).  Writes the n_new new tokens' rows k_new, v_new [B, Hkv, n_new, d]
+ * Decode-step cache maintenance in one launch (Sec. 4.2: a decode step extends
+ * the label cache by the new tokens' r selected channels only).  Writes the n_new new tokens' rows k_new, v_new [B, Hkv, n_new, d]
  * fp16 (device, 16-byte aligned) into the caches at tokens [t0, t0 + n_new) and
  * label[b, h, t0 + i, j] = k_new[b, h, i, channels[h, j]].  With
  * DS_KV_INTERLEAVED pass the KV array as K; V is ignored.  Uses
@@ -308,13 +307,10 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  *           tokens -- more than 4K when the attention launch can score as well, see knob 4 --
  *           and for units short enough for one workgroup each: up to 4K tokens, up to 8K when
  *           there are 256 units or more; else 1), 1 = three launches
- *           (score, candidates, attend), 2 = one launch of co-resident worker and reducer
- *           workgroups when the shape and the device allow it (else three launches),
- *           3 = two launches: that co-resident launch up to the threshold candidates, then
- *           one attention launch in which every workgroup settles its unit's exact threshold,
- *           4 = two launches: scoring (keys and threshold bin), then one launch in which a
- *           unit's workgroups attend the rows above the threshold bin while the last of them
- *           to have listed its candidates settles the exact threshold for the rest
+ *           (score, candidates, attend), 4 = scoring (keys and threshold bin), then one launch
+ *           in which a unit's workgroups attend the rows above the threshold bin while the last
+ *           of them to have listed its candidates settles the exact threshold for the rest
+ *           (one launch in all when that launch can score as well, see knob 4)
  *   knob 4: where the exact top-k threshold is settled on the three-launch path: 0 = automatic
  *           (in the scoring launch for units of up to 8K tokens), 1 = always in a separate
  *           candidate launch, 2 = always in the scoring launch.  On launch shape 4 with a label

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsattn.so")
-SOURCES = ["ds_select.hip", "ds_attend.hip", "ds_fused.hip", "ds_misc.hip", "ds_api.cpp"]
+SOURCES = ["ds_select.hip", "ds_attend.hip", "ds_misc.hip", "ds_api.cpp"]
 HEADERS = ["ds_internal.h", "ds_device.h", "ds_attend_core.h"]
 
 FLAGS = [

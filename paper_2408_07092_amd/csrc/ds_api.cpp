@@ -133,9 +133,7 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
     p->off_ndef = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
     p->off_offs = off;  off = align_up(off + (size_t)p->units * p->n_ch * 4, 256);
     p->off_part = off;  off = align_up(off + (size_t)p->units * p->G * p->n_ch * kPartStride * 4, 256);
-    // the single-launch path shares the control prefix and lays its own data after it
-    p->off_fused = p->off_keys;
-    p->total = std::max(off, align_up(p->off_fused + fused_workspace_bytes(s, *p), 256));
+    p->total = off;
     return true;
 }
 
@@ -165,7 +163,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
 // ---------------------------------------------------------------- per-kernel event timing
 static const char *const kKernelNames[KID_COUNT] = {
     "k_init", "k_score", "k_cand", "k_attend", "k_compact", "k_dense",
-    "k_attend_rows", "k_label", "k_gather_host", "k_probe", "k_fused", "k_attend2",
+    "k_attend_rows", "k_label", "k_gather_host", "k_probe",
     "k_refine_attend", "k_append_kv", "k_q4_amax", "k_q4_write", "k_predict_query"};
 
 struct ProfRec { int id; hipEvent_t a, b; };
@@ -453,12 +451,6 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    FusedPlan f;
-    if (src.kind == SRC_LABEL && kv_stride == kD && make_fused_plan(*shape, p, &f)) {
-        if (tune_get(3) == 3) DS_TRY(launch_two(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st));
-        else DS_TRY(launch_fused(q, label, K, V, channels, workspace, out, idx_out, p, f, *shape, st, 0));
-        return DS_OK;
-    }
     // a workgroup that may score its tokens itself: one launch, keys never leave LDS
     // ... and so can several workgroups per unit (their chunk histograms meet in memory and the
     // threshold bin is published to them) as long as the whole grid is resident at once: single
@@ -665,7 +657,7 @@ ds_status_t ds_tune_set(int knob, int value)
         if (knob == 0 && (value % 256 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
         if (knob == 1 && (value % 64 != 0 || value > 16384)) return DS_ERR_SHAPE;
         if (knob == 2 && (value % 16 != 0 || value > (1 << 20))) return DS_ERR_SHAPE;
-        if (knob == 3 && value > 4) return DS_ERR_SHAPE;
+        if (knob == 3 && value != 1 && value != 4) return DS_ERR_SHAPE;
         if (knob == 4 && value > 2) return DS_ERR_SHAPE;
     }
     g_tune[knob] = value;

@@ -1,5 +1,5 @@
-// Attention building blocks shared by the per-chunk attention kernel and the
-// fused decode kernel (Algorithm 1 steps 3-5 / Sec. 2.1).
+// Attention building blocks of the attention kernels
+// (Algorithm 1 steps 3-5 / Sec. 2.1).
 //
 // Row processing: a wavefront loads four rows per instruction -- 16 lanes x 16
 // bytes cover one 256-byte row -- so each 16-lane group ("slot") owns a row at

@@ -50,8 +50,6 @@ enum KernelId {
     KID_LABEL,
     KID_GATHER_HOST,
     KID_PROBE,
-    KID_FUSED,
-    KID_ATTEND2,
     KID_REFINE_ATTEND,
     KID_APPEND_KV,
     KID_Q4_AMAX,
@@ -69,14 +67,7 @@ struct Plan {
     bool refine_attend;  // ds_sparse_decode as scoring + one refine-and-attend launch
     bool group_scores_itself;  // query groups of 3+ heads: chunks sized so that this launch can do the scoring too
     size_t off_ctl, off_hist, off_coarse, off_keys, off_cand, off_ndef, off_offs, off_part;
-    size_t off_fused;    // data region of the single-launch path (same control prefix)
     size_t total;
-};
-// Launch shape of the single-launch path, decided at launch time from the device's capacity.
-struct FusedPlan {
-    bool ok;
-    int P, n_svc, n_ch, items, max_items, rmode;
-    size_t lds;
 };
 // Plan of dense / gathered-rows attention (token chunks of dn_chunk).
 struct DensePlan {
@@ -98,10 +89,7 @@ struct ScoreSrc {
 enum PlanFor { PLAN_SELECT = 0, PLAN_DECODE = 1, PLAN_DECODE_SCORING = 2 };
 bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose = PLAN_SELECT);
 bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);
-bool make_fused_plan(const ds_shape_t &s, const Plan &p, FusedPlan *f);
-size_t fused_workspace_bytes(const ds_shape_t &s, const Plan &p);
 
-// profiling hooks (ds_profile.cpp)
 // Per-kernel timing: while it is on, prof_events hands out a start and a stop event for one
 // launch of kernel `id` (false when it is off or no event could be made) and remembers the pair.
 bool prof_events(int id, hipEvent_t *start, hipEvent_t *stop);
@@ -140,12 +128,6 @@ hipError_t launch_append_kv(const void *k_new, const void *v_new, void *K, void 
                             int kv_stride, hipStream_t st);
 hipError_t launch_gather_host(const void *Kh, const void *Vh, const int32_t *idx, void *rows,
                               const ds_shape_t &s, hipStream_t st);
-hipError_t launch_fused(const void *q, const void *label, const void *K, const void *V,
-                        const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
-                        const FusedPlan &f, const ds_shape_t &s, hipStream_t st, int two_launch);
-hipError_t launch_two(const void *q, const void *label, const void *K, const void *V,
-                      const int32_t *channels, void *ws, float *out, int32_t *idx_out, const Plan &p,
-                      const FusedPlan &f, const ds_shape_t &s, hipStream_t st);
 hipError_t launch_probe(const void *src, size_t bytes, uint32_t *sink, hipStream_t st);
 
 int tune_get(int knob);

@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kWG) void k_label(const uint16_t *__restrict__ K,
     }
 }
 
-// Decode-step cache maintenance in one launch (Sec. 4.2: in decoding only the new tokens'
-// heavy-channel values are added to the label cache): the n new tokens' K and V rows go into
+// Decode-step cache maintenance in one launch (Sec. 4.2: a decode step extends the label cache
+// by the new tokens' r selected channels only): the n new tokens' K and V rows go into
 // the caches at tokens [t0, t0 + n) and their r label values into the label cache.
 // 16 lanes move one 256-byte row; the label values are picked out of the new rows afterwards.
 __global__ __launch_bounds__(kWG) void k_append_kv(const uint4 *__restrict__ k_new,

@@ -17,12 +17,11 @@ from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_n
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["one_launch", "two_launch", "score_tail", "cand_launch", "refine_attend", "unit_fused", "unit_fused_big",
+@pytest.fixture(params=["score_tail", "cand_launch", "refine_attend", "unit_fused", "unit_fused_big",
                         "chunks_fused", "auto"],
                 autouse=True)
 def decode_path(request):
-    """Every test runs on every implementation of ds_sparse_decode: the single
-    launch (workers + reducers), the co-resident two-launch path, the
+    """Every test runs on every implementation of ds_sparse_decode: the
     three-launch path with the exact threshold settled either in the scoring
     launch's tail or in a candidate launch of its own, scoring followed by the
     launch that refines the threshold behind the attention, that launch with one
@@ -30,7 +29,7 @@ def decode_path(request):
     to that length; chunks of 16384 tokens: the variant of a workgroup that has a CU to
     itself), the same with several scoring workgroups per unit, and the library's own
     choice."""
-    mode, refine, chunk, _ = {"one_launch": (2, 0, 0, 0), "two_launch": (3, 0, 0, 0), "score_tail": (1, 2, 0, 0),
+    mode, refine, chunk, _ = {"score_tail": (1, 2, 0, 0),
                                   "cand_launch": (1, 1, 0, 0), "refine_attend": (4, 1, 0, 0), "unit_fused": (4, 0, 6144, 0),
                                   "unit_fused_big": (4, 0, 16384, 0),
                                   "chunks_fused": (4, 2, 0, 0), "auto": (0, 0, 0, 0)}[request.param]

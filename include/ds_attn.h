@@ -200,6 +200,31 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K,
                              void *stream);
 
 /*
+ * ds_sparse_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The scratch is a device array inside the library
+ * (ds_static_scratch_bytes() = 32 MiB, held once per GPU for the life of the
+ * process); this call allocates and frees nothing, and neither does anything it
+ * calls.  Same arguments, results (bit for bit) and errors as ds_sparse_decode,
+ * minus the workspace; a shape whose scratch layout exceeds the array is refused
+ * with DS_ERR_WORKSPACE and nothing is enqueued (the headline shape B = 1, 32
+ * heads, L = 65536 needs 25 MiB; 12 bytes per cached token of all units plus
+ * 20 KiB per unit is a safe estimate).  Every call first clears the control part
+ * of the scratch with a fill kernel on `stream`, so calls of different shapes may
+ * follow each other.  All calls on one GPU share the one array: calls that overlap
+ * in time on the same GPU (different streams, different threads) race and give
+ * wrong results; serialise them.  ds_static_init() resolves the array's address
+ * on the current device ahead of time (optional; the first call does it
+ * otherwise); call it once per device before capturing.
+ */
+size_t ds_static_scratch_bytes(void);
+ds_status_t ds_static_init(void);
+ds_status_t ds_sparse_decode_static(const void *q, const void *label, const void *K,
+                                    const void *V, const int32_t *channels, float *out,
+                                    int32_t *idx_out, const ds_shape_t *shape,
+                                    void *stream);
+
+/*
  * The same decode without a label cache (Sec. 4.2 and the appendix ablation
  * "Forward without Label Cache"): s_hat[t] is formed from K[t, channels[j]] read
  * out of the 256-byte K rows, the strided access the label cache removes.  Same

@@ -24,6 +24,7 @@ DS_KV_SPLIT, DS_KV_INTERLEAVED = 0, 1
 EXPORTS = [
     "ds_strerror", "ds_version", "ds_calibrate_channels", "ds_build_label", "ds_append_label",
     "ds_workspace_bytes", "ds_workspace_init", "ds_workspace_errors", "ds_sparse_decode", "ds_sparse_decode_nolabel",
+    "ds_static_scratch_bytes", "ds_static_init", "ds_sparse_decode_static",
     "ds_sparse_decode_kv", "ds_append_kv", "ds_build_label_kv", "ds_build_label_q4",
     "ds_append_label_q4", "ds_sparse_decode_q4", "ds_predict_query", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
@@ -67,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.ds_workspace_init.argtypes = [vp, sz, vp]
         L.ds_workspace_errors.argtypes = [vp, sz, shp, vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         L.ds_sparse_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
+        L.ds_static_scratch_bytes.restype = sz
+        L.ds_static_scratch_bytes.argtypes = []
+        L.ds_static_init.argtypes = []
+        L.ds_sparse_decode_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, shp, vp]
         L.ds_sparse_decode_nolabel.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_sparse_decode_kv.argtypes = [vp, vp, vp, vp, vp, vp, vp, sz, shp, vp]
         L.ds_append_kv.argtypes = [vp, vp, vp, vp, vp, vp, shp, i32, i32, ctypes.c_int, vp]
@@ -183,6 +188,20 @@ def ds_sparse_decode(q, label, K, V, channels, out, idx_out, workspace, shp: DsS
                                   _dp(idx_out), _dp(workspace),
                                   workspace.numel() * workspace.element_size(),
                                   ctypes.byref(shp), _stream(stream)), "ds_sparse_decode")
+
+
+def ds_static_scratch_bytes() -> int:
+    return int(lib().ds_static_scratch_bytes())
+
+
+def ds_static_init():
+    _check(lib().ds_static_init(), "ds_static_init")
+
+
+def ds_sparse_decode_static(q, label, K, V, channels, out, idx_out, shp: DsShape, stream=None):
+    _check(lib().ds_sparse_decode_static(_dp(q), _dp(label), _dp(K), _dp(V), _dp(channels), _dp(out),
+                                         _dp(idx_out), ctypes.byref(shp), _stream(stream)),
+           "ds_sparse_decode_static")
 
 
 def ds_sparse_decode_nolabel(q, K, V, channels, out, idx_out, workspace, shp: DsShape, stream=None):

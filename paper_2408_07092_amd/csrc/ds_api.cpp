@@ -8,7 +8,15 @@
 #include <mutex>
 #include <vector>
 
+#include <hip/hip_runtime.h>
+
 #include "ds_internal.h"
+
+// Scratch of ds_sparse_decode_static: device memory that the library itself holds, one copy per
+// GPU from the moment the code object is loaded there until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+#define DS_STATIC_SCRATCH_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[DS_STATIC_SCRATCH_BYTES];
 
 namespace ds {
 
@@ -219,7 +227,7 @@ const char *ds_strerror(ds_status_t status)
     case DS_ERR_NULL: return "required pointer is NULL";
     case DS_ERR_SHAPE: return "invalid shape or size argument";
     case DS_ERR_ALIGN: return "pointer is not sufficiently aligned";
-    case DS_ERR_WORKSPACE: return "workspace is too small";
+    case DS_ERR_WORKSPACE: return "workspace is too small (static-scratch call: the shape needs more than ds_static_scratch_bytes())";
     case DS_ERR_UNSUPPORTED: return "configuration not supported";
     case DS_ERR_HIP: return "HIP runtime reported an error";
     }
@@ -434,7 +442,7 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
                                       const int32_t *channels, float *out, int32_t *idx_out,
                                       void *workspace, size_t workspace_bytes,
                                       const ds_shape_t *shape, void *stream, ScoreSrc src,
-                                      int kv_stride = kD)
+                                      int kv_stride = kD, bool clear_first = false)
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
@@ -451,6 +459,9 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     if (!aligned(K, 256) || !aligned(V, 256) || !aligned(out, 16) || (idx_out && !aligned(idx_out, 16)))
         return DS_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
+    // (a workspace shared by calls of different shapes: counters, histograms and error words start
+    //  from zero whatever the last call left there -- a fill kernel, so that the call can be captured)
+    if (clear_first) DS_TRY(launch_init(workspace, p.off_keys, st));
     // a workgroup that may score its tokens itself: one launch, keys never leave LDS
     // ... and so can several workgroups per unit (their chunk histograms meet in memory and the
     // threshold bin is published to them) as long as the whole grid is resident at once: single
@@ -485,6 +496,45 @@ ds_status_t ds_sparse_decode(const void *q, const void *label, const void *K, co
 {
     return sparse_decode_impl(q, label, K, V, channels, out, idx_out, workspace, workspace_bytes, shape,
                               stream, ScoreSrc());
+}
+
+// Address of this device's copy of the static scratch array, resolved once per device.
+static ds_status_t static_scratch(void **ptr)
+{
+    static std::mutex mu;
+    static void *per_device[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DS_ERR_HIP;
+    if (dev < 0 || dev >= 64) return DS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DS_ERR_HIP;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return DS_OK;
+}
+
+size_t ds_static_scratch_bytes(void) { return DS_STATIC_SCRATCH_BYTES; }
+
+ds_status_t ds_static_init(void)
+{
+    void *p = nullptr;
+    return static_scratch(&p);
+}
+
+ds_status_t ds_sparse_decode_static(const void *q, const void *label, const void *K, const void *V,
+                                    const int32_t *channels, float *out, int32_t *idx_out,
+                                    const ds_shape_t *shape, void *stream)
+{
+    if (!q || !label || !K || !V || !channels || !out || !shape) return DS_ERR_NULL;
+    void *ws = nullptr;
+    ds_status_t rc = static_scratch(&ws);
+    if (rc != DS_OK) return rc;
+    // shapes whose scratch layout is larger than the array come back as DS_ERR_WORKSPACE
+    return sparse_decode_impl(q, label, K, V, channels, out, idx_out, ws, DS_STATIC_SCRATCH_BYTES, shape,
+                              stream, ScoreSrc(), kD, true);
 }
 
 ds_status_t ds_sparse_decode_nolabel(const void *q, const void *K, const void *V,

@@ -55,6 +55,9 @@ def parse():
                     help="C5: select with queries predicted from the previous layer's embedding (W_q GEMV on the select stream)")
     ap.add_argument("--label-bits", type=int, default=16, choices=(16, 4),
                     help="label cache precision: fp16 (the metric's configuration) or the 4-bit cache")
+    ap.add_argument("--trace", action="store_true",
+                    help="stage stamps of the attention launch: loads the -DDS_TRACE build of the library, runs a few "
+                         "layers and prints, per stage, when the workgroups of the last launch reached it")
     ap.add_argument("--label-ablation", action="store_true",
                     help="with / without label cache over the batch x length grid of the paper's ablation table")
     return ap.parse_args()
@@ -70,6 +73,11 @@ def main():
     import numpy as np
     import torch
 
+    if args.trace:
+        from paper_2408_07092_amd import binding, build as ds_build
+        if not os.path.exists(ds_build.LIB_TRACE):
+            sys.exit("bench.py --trace: build the stage-stamp library first (python -m paper_2408_07092_amd.build --trace)")
+        binding.LIB_PATH = ds_build.LIB_TRACE
     import paper_2408_07092_amd as ds
     from workloads import WORKLOADS, make_calibration_numpy, make_layer_torch
 
@@ -126,6 +134,9 @@ def main():
                 ds.ds_sparse_decode_q4(q, label[0], label[1], K, V, ch, out, None, ws, shp)
             else:
                 ds.ds_sparse_decode(q, label, K, V, ch, out, None, ws, shp)
+
+    if args.trace:
+        return trace_report(args, w, ds, torch, sparse_sweep)
 
     def nolabel_sweep():
         for (q, label, K, V, ch) in layers:
@@ -282,6 +293,57 @@ def main():
                                "sample": f"{reps} layer passes over {n_host} layers of {w.name} (all {w.units} units each), {t_cpu:.1f} s of CPU time"}
     res["extra"] = extra
     print(json.dumps(res))
+
+
+# Stage numbers that thread 0 of every workgroup of the attention launch stamps (DS_TR in
+# csrc/ds_attend.hip), in the order a workgroup passes them.
+TRACE_STAGES = [(0, "start"), (11, "chunk scored (keys in LDS)"), (12, "unit histogram complete"),
+                (10, "threshold bin known"), (1, "lists made, candidates handed over"), (2, "arrived at unit counter"),
+                (8, "refiner: candidates loaded"), (9, "refiner: exact threshold published"),
+                (3, "definite rows attended"), (4, "exact threshold picked up, rest listed"),
+                (5, "remaining rows attended"), (6, "partial written, arrived"), (7, "unit merged")]
+
+
+def trace_report(args, w, ds, torch, sweep):
+    """Runs three sweeps with the stage-stamp build and prints, for the last launch, when its
+    workgroups reached each stage (us after the first workgroup started; the device's 100 MHz
+    wall clock), and how long the stage took in the workgroups that passed it."""
+    import ctypes
+
+    import numpy as np
+    for _ in range(3):
+        sweep()
+    torch.cuda.synchronize()
+    n_slots = 1 << 14
+    buf = np.zeros(n_slots * 16, dtype=np.int64)
+    rc = ds.lib().ds_trace_read_attend(ctypes.c_void_p(buf.ctypes.data), ctypes.c_size_t(buf.nbytes))
+    assert rc == 0, "ds_trace_read_attend failed"
+    tr = buf.reshape(n_slots, 16).astype(np.float64) / 100.0
+    live = tr[:, 0] > 0
+    # stamps of the last launch: within 500 us of the latest start
+    t_last = tr[live, 0].max()
+    wg = live & (tr[:, 0] > t_last - 500.0)
+    t0 = tr[wg, 0].min()
+    print(f"# stage stamps, workload {w.name}, {int(wg.sum())} workgroups in the last launch; us since the first workgroup started")
+    print(f"# {'stage':44s} {'n':>5s} {'min':>7s} {'p10':>7s} {'p50':>7s} {'p90':>7s} {'max':>7s}   since previous stage: p50 / max")
+    prev = None
+    for st, name in TRACE_STAGES:
+        ok = wg & (tr[:, st] >= t0)
+        if not ok.any():
+            continue
+        c = tr[ok, st] - t0
+        line = (f"  {name:44s} {int(ok.sum()):5d} {c.min():7.2f} {np.percentile(c, 10):7.2f} {np.median(c):7.2f} "
+                f"{np.percentile(c, 90):7.2f} {c.max():7.2f}")
+        if prev is not None:
+            both = ok & (tr[:, prev] >= t0)
+            if both.any():
+                d = tr[both, st] - tr[both, prev]
+                line += f"   {np.median(d):6.2f} / {d.max():6.2f}"
+        print(line)
+        if int(ok.sum()) > int(wg.sum()) // 2:
+            prev = st
+    end = max(tr[wg, st].max() for st, _ in TRACE_STAGES) - t0
+    print(f"# last stamp of the launch at {end:.2f} us")
 
 
 def bench_label_ablation(args, ds, torch, dev):

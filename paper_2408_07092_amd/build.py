@@ -9,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsattn.so")
+# the same library with the in-kernel stage stamps compiled in (bench.py --trace loads it)
+LIB_TRACE = os.path.join(HERE, "libdsattn_trace.so")
 SOURCES = ["ds_select.hip", "ds_attend.hip", "ds_misc.hip", "ds_api.cpp"]
 HEADERS = ["ds_internal.h", "ds_device.h", "ds_attend_core.h"]
 
@@ -36,16 +38,17 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > t for p in deps)
 
 
-def build(verbose: bool = True) -> str:
-    """Compile every source and link the shared library; always recompiles."""
+def build(verbose: bool = True, trace: bool = False) -> str:
+    """Compile every source and link the shared library; always recompiles.  With `trace` the
+    stage-stamp variant (-DDS_TRACE) is built instead, into LIB_TRACE."""
     cc = hipcc()
     objs = []
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.path.join(HERE, "_build", "trace" if trace else "plain")
     os.makedirs(bdir, exist_ok=True)
     procs = []
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")
-        cmd = [cc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc] + FLAGS + (["-DDS_TRACE"] if trace else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if src.endswith(".cpp"):
             cmd.insert(1, "-x"); cmd.insert(2, "hip")
         if verbose:
@@ -55,13 +58,13 @@ def build(verbose: bool = True) -> str:
     for src, p in procs:
         if p.wait() != 0:
             raise RuntimeError(f"hipcc failed on {src}")
-    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    lib = LIB_TRACE if trace else LIB
+    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    build()
-    print(LIB)
+    print(build(trace="--trace" in sys.argv[1:]))

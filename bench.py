@@ -299,7 +299,9 @@ def main():
 # csrc/ds_attend.hip), in the order a workgroup passes them.
 TRACE_STAGES = [(0, "start"), (11, "chunk scored (keys in LDS)"), (12, "unit histogram complete"),
                 (10, "threshold bin known"), (1, "lists made, candidates handed over"), (2, "arrived at unit counter"),
-                (8, "refiner: candidates loaded"), (9, "refiner: exact threshold published"),
+                (8, "refiner: candidate loads issued"),
+                (14, "refiner: first radix pass done"), (15, "refiner: exact threshold known"),
+                (9, "refiner: published, histograms cleared"),
                 (3, "definite rows attended"), (4, "exact threshold picked up, rest listed"),
                 (5, "remaining rows attended"), (6, "partial written, arrived"), (7, "unit merged")]
 

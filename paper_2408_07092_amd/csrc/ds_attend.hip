@@ -16,6 +16,18 @@
 
 #include "ds_attend_core.h"
 
+#ifndef DS_MC_RPS
+#define DS_MC_RPS 4
+#endif
+#ifndef DS_NO_PRIO
+#define DS_PRIO(x) __builtin_amdgcn_s_setprio(x)
+#else
+#define DS_PRIO(x) do { } while (0)
+#endif
+#ifndef DS_SC_DEPTH
+#define DS_SC_DEPTH 8
+#endif
+
 namespace ds {
 
 DS_TRACE_BUFFER
@@ -200,7 +212,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     uint32_t *keys_sh = dyn_sh;
     uint16_t *sel = reinterpret_cast<uint16_t *>(dyn_sh + a.ch);
     uint32_t *cnt = dyn_sh + a.ch + a.ch / 2;
-    __shared__ uint32_t s_w[NW], s_flag, s_res[2], s_base, s_T[2], s_ok;
+    __shared__ uint32_t s_w[NW], s_flag, s_res[2], s_base, s_T[2], s_ok, s_cnt2;
     __shared__ float red_ml[8][2];
     __shared__ __attribute__((aligned(16))) _Float16 qsh[GT >= 4 ? 1 : GT][kD];
     __shared__ __attribute__((aligned(16))) float sc_sh[4][16];
@@ -307,11 +319,12 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         }
         if constexpr (!kQ4) {
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
-        half8 v[8][NV];
+        constexpr int SD = DS_SC_DEPTH;
+        half8 v[SD][NV];
         // (rows past the end of the chunk re-read its last row; their scores are dropped)
         auto issue = [&](int tb) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < SD; ++i) {
                 const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * WGT, t1 - 1) * SMODE);
 #pragma unroll
                 for (int j = 0; j < NV; ++j) v[i][j] = row[j];
@@ -344,7 +357,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         for (int j = 0; j < SMODE; ++j) qs[j] = qs_sh[j];
         for (int tb = t0 + tid; tb < t1;) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < SD; ++i) {
                 float acc = 0.0f;
 #pragma unroll
                 for (int j = 0; j < NV; ++j)
@@ -357,10 +370,11 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                     atomicAdd(&hist_at(key >> kKeyShift), 1u);
                 }
             }
-            tb += WGT * 8;
+            tb += WGT * SD;
             if (tb < t1) issue(tb);
         }
         }  // fp16 labels
+        DS_PRIO(3);
         __syncthreads();
         DS_TR(11);
         if (gridDim.x == 1) {
@@ -697,33 +711,72 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 for (uint32_t i = tid; i < n; i += WGT) f(cand_at(i));
             }
         };
+        if (tid == 0) s_cnt2 = 0u;  // (pass 1 has barriers before its first use)
         DS_TR(8);
         uint32_t krem = krem_unit;
         svc_radix_pass<1024 / WGT, true, NW>(each, [](uint2) { return true; },
                                 [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
         const uint32_t pre22 = (bstar << 10) | s_res[0];
         krem = s_res[1];
+        const uint32_t n22 = lh[s_res[0]];  // candidates that share the k-th key's 22-bit prefix
         __syncthreads();
-        svc_radix_pass<1024 / WGT, true, NW>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
-                                [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
-        T = (pre22 << 10) | s_res[0];
-        const uint32_t m_ties = s_res[1];
-        const uint32_t n_ties = lh[s_res[0]];
-        __syncthreads();
-        if (m_ties < n_ties) {
-            svc_radix_pass<1, false, NW>(each, [&](uint2 e) { return e.x == T; },
-                                     [](uint2 e) { return (e.y >> 20) & 255u; }, m_ties, lh, s_w, s_res);
-            uint32_t prefix = s_res[0], want = s_res[1];
+        DS_TR(14);
+        bool settled = false;
+        if (n22 <= 64u) {
+            // One or two candidates as a rule: they are ranked among themselves by one wavefront,
+            // in the order (key descending, token ascending); the one of rank krem is the unit's
+            // k-th key, and its token is the tie cut.
+            __shared__ uint2 s_small[64];
+            each([&](uint2 e) {
+                if ((e.x >> 10) == pre22) {
+                    const uint32_t slot = atomicAdd(&s_cnt2, 1u);
+                    if (slot < 64u) s_small[slot] = e;
+                }
+            });
             __syncthreads();
-            svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
-                                     [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
-            prefix = (prefix << 10) | s_res[0];
-            want = s_res[1];
+            const uint32_t m = min(s_cnt2, 64u);
+            if (tid < 64 && (uint32_t)tid < m) {
+                const uint2 mine = s_small[tid];
+                uint32_t before = 0;
+                for (uint32_t j = 0; j < m; ++j) {
+                    const uint2 o = s_small[j];
+                    before += (o.x > mine.x || (o.x == mine.x && o.y < mine.y)) ? 1u : 0u;
+                }
+                if (before + 1u == krem) {
+                    s_T[0] = mine.x;
+                    s_T[1] = mine.y;
+                }
+            }
             __syncthreads();
-            svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
-                                     [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
-            tcut = (int)((prefix << 10) | s_res[0]);
+            // (counts that do not add up mean a workspace that was not cleared: take the long way)
+            if (m == n22 && krem >= 1u && krem <= m) {
+                T = s_T[0];
+                tcut = (int)s_T[1];
+                settled = true;
+            }
+        }
+        if (!settled) {
+            svc_radix_pass<1024 / WGT, true, NW>(each, [&](uint2 e) { return (e.x >> 10) == pre22; },
+                                    [](uint2 e) { return e.x & 1023u; }, krem, lh, s_w, s_res);
+            T = (pre22 << 10) | s_res[0];
+            const uint32_t m_ties = s_res[1];
+            const uint32_t n_ties = lh[s_res[0]];
             __syncthreads();
+            if (m_ties < n_ties) {
+                svc_radix_pass<1, false, NW>(each, [&](uint2 e) { return e.x == T; },
+                                         [](uint2 e) { return (e.y >> 20) & 255u; }, m_ties, lh, s_w, s_res);
+                uint32_t prefix = s_res[0], want = s_res[1];
+                __syncthreads();
+                svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 20) == prefix; },
+                                         [](uint2 e) { return (e.y >> 10) & 1023u; }, want, lh, s_w, s_res);
+                prefix = (prefix << 10) | s_res[0];
+                want = s_res[1];
+                __syncthreads();
+                svc_radix_pass<1024 / WGT, false, NW>(each, [&](uint2 e) { return e.x == T && (e.y >> 10) == prefix; },
+                                         [](uint2 e) { return e.y & 1023u; }, want, lh, s_w, s_res);
+                tcut = (int)((prefix << 10) | s_res[0]);
+                __syncthreads();
+            }
         }
         if (a.idx_out && !single) {
             // selected tokens per chunk = keys above b* + selected candidates; prefix -> offsets
@@ -746,6 +799,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
+        DS_TR(15);
         if (!single && tid == 0) {
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             __hip_atomic_store(cand_arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -753,16 +807,6 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         if constexpr (SMODE != 0 && !kAllFind) {
             // every workgroup of the unit has arrived, so all of them have read the threshold bin
             if (!single && tid == 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
-        }
-        if constexpr (SMODE != 0 && kAllFind) {
-            // every workgroup of the unit has arrived here, so all of them have read the unit's
-            // histograms and their arrival counter: clean for the next call
-            if (!single) {
-                uint32_t *hu = a.hist + (size_t)u * kHistBins;
-                for (int i = tid; i < kHistBins; i += WGT) hu[i] = 0u;
-                a.coarse[(size_t)u * 256 + tid] = 0u;
-                if (tid == 0) ctl->arrive_a = 0u;
-            }
         }
         DS_TR(9);
     }
@@ -901,9 +945,13 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             __syncthreads();
             RowState<GT> st;
             st.init();
+            DS_PRIO(0);
             attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
+            DS_PRIO(3);
             if (g0 == 0) { DS_TR(3); settle(); }
+            DS_PRIO(2);
             attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
+            DS_PRIO(3);
             DS_TR(5);
             wg_store_partial<GT, NW>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
         }
@@ -925,6 +973,14 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         merge_partials(a.part + (size_t)u * a.G * a.n_ch * kPartStride, a.G, a.n_ch,
                        a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
     DS_TR(7);
+    if constexpr (SMODE != 0 && kAllFind && NW == 4) {
+        // every workgroup of the unit has long read the unit's histograms and passed their arrival
+        // counter: clean for the next call (off everybody's path but the launch's very end)
+        uint4 *hu = reinterpret_cast<uint4 *>(a.hist + (size_t)u * kHistBins);
+        for (int i = tid; i < kHistBins / 4; i += WGT) hu[i] = make_uint4(0u, 0u, 0u, 0u);
+        a.coarse[(size_t)u * 256 + tid] = 0u;
+        if (tid == 0) ctl->arrive_a = 0u;
+    }
 }
 
 // ---------------------------------------------------------------- launchers
@@ -1069,8 +1125,8 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     } while (0)
 #define DS_RA(GTV)                                                                                     \
     do {                                                                                               \
-        if (smode == 0) DS_RA_ONE(GTV, 0, 4);                                                           \
-        else DS_RA_SM(GTV, 4);                                                                          \
+        if (smode == 0) DS_RA_ONE(GTV, 0, DS_MC_RPS);                                                   \
+        else DS_RA_SM(GTV, DS_MC_RPS);                                                                       \
     } while (0)
     if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10) && p.n_ch == 1) {
         // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot

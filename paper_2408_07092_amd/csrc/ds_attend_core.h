@@ -152,18 +152,20 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
-            // the rows of a slot are folded into its state four at a time, in row order, so that
-            // the result does not depend on RPS
+            // the rows of a slot are folded into its state four at a time (fewer when fewer are in
+            // flight), in row order
+            constexpr int FG = RPS < 4 ? RPS : 4;
 #pragma unroll
-            for (int i0 = 0; i0 < RPS; i0 += 4) {
-                float s[4];
+            for (int i0 = 0; i0 < RPS; i0 += FG) {
+                float s[FG];
+                float mx = kNegInf;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < FG; ++i) {
                     s[i] = row16_sum(dot8(qv, kr[i0 + i])) * kScaleLog2;
                     if (!ok[i0 + i]) s[i] = kNegInf;
+                    mx = fmaxf(mx, s[i]);
                 }
                 // a slot may have no valid row yet (m stays -inf); slot 0 always has one here
-                const float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
                 const float mn = fmaxf(st.m[g], mx);
                 if (mn != kNegInf) {
                     const float sc = (st.m[g] == kNegInf) ? 0.0f : __builtin_amdgcn_exp2f(st.m[g] - mn);
@@ -172,7 +174,7 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 #pragma unroll
                     for (int j = 0; j < 8; ++j) st.acc[g][j] *= sc;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
+                    for (int i = 0; i < FG; ++i) {
                         const float p = __builtin_amdgcn_exp2f(s[i] - mn);  // 2^-inf = 0 for masked rows
                         st.l[g] += p;
 #pragma unroll

@@ -291,6 +291,10 @@ def main():
         res["cpu_baseline"] = {"value": round(t_cpu / reps * 1e6, 1), "unit": "us/layer", "cores": cores,
                                "kind": "oracle",
                                "sample": f"{reps} layer passes over {n_host} layers of {w.name} (all {w.units} units each), {t_cpu:.1f} s of CPU time"}
+    # ---- no bounded wait between workgroups may have run out in any of the launches above
+    n_failed, code = ds.ds_workspace_errors(ws, shp)
+    if n_failed:
+        sys.exit(f"bench.py: {n_failed} unit(s) raised error word {code} (a wait between workgroups ran out): no metric")
     res["extra"] = extra
     print(json.dumps(res))
 

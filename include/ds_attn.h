@@ -28,8 +28,10 @@
  *     workspace carries a few counters that every call leaves at zero again, so
  *     it must be cleared once with ds_workspace_init() after allocation, must
  *     not be written by the caller, and must be cleared again before it is used
- *     with a different shape or after a call that returned DS_ERR_HIP.  Two
- *     calls that overlap in time must not share a workspace.
+ *     with a different shape, after a call that returned DS_ERR_HIP or after a
+ *     call whose output came back as NaN (see ds_workspace_errors).  Two calls
+ *     that overlap in time must not share a workspace, and a decode call expects
+ *     the device to itself while it runs.
  *   - Device entry points only enqueue work on `stream` (a hipStream_t passed
  *     as void*, NULL = the null stream) and return without synchronising.
  *     DS_OK means "validated and enqueued".
@@ -170,12 +172,20 @@ size_t ds_workspace_bytes(const ds_shape_t *shape);
 ds_status_t ds_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 /* Waits for `stream` and reads back the per-unit error words of the workspace
  * (DEVICE pointer) for this shape.  Inside a launch a workgroup sometimes waits
- * for another workgroup of its unit (Algorithm 1 steps 2-5 done in one launch);
- * every such wait is bounded, and a workgroup whose wait runs out raises its
- * unit's error word and carries on without the value it waited for -- the launch
- * always ends, but that unit's result is then not the top-k attention.  The word
- * stays set until ds_workspace_init().  *n_failed = units whose word is set,
- * *first_code = the first such word (which wait it was; 0 if none); either
+ * for another workgroup of its unit (Algorithm 1 steps 2-5 done in one launch).
+ * The library only enqueues such a launch when the occupancy that the runtime
+ * reports for the kernel holds all the workgroups that wait for each other at the
+ * same time (otherwise it takes launch shapes that need less, down to three
+ * launches that need nothing); that figure assumes that the decode call has the
+ * device to itself -- kernels of other streams or processes that occupy compute
+ * units while it runs can keep workgroups from starting.  Every wait is therefore
+ * bounded as well: a workgroup whose wait runs out raises its unit's error word
+ * and carries on without the value it waited for, the launch always ends, and
+ * that unit's rows of `out` are written as NaN instead of a wrong result.  The
+ * word stays set until ds_workspace_init(): later calls on the workspace write
+ * NaN for that unit again without computing it, so the failure cannot pass
+ * unnoticed by a caller that never asks here.  *n_failed = units whose word is
+ * set, *first_code = the first such word (which wait it was; 0 if none); either
  * pointer may be NULL.  DS_OK when the words could be read (whatever they say),
  * DS_ERR_HIP when the copy failed.  Synchronises: not for the hot path. */
 ds_status_t ds_workspace_errors(const void *workspace, size_t workspace_bytes,
@@ -354,6 +364,25 @@ ds_status_t ds_profile_read(int id, double *total_ms, int64_t *launches);
  */
 ds_status_t ds_tune_set(int knob, int value);
 int ds_tune_get(int knob);
+
+/*
+ * How ds_sparse_decode would be launched for a shape (diagnostics and tests; pure host work
+ * apart from asking the runtime for the kernel's occupancy).  label_kind: 0 = fp16 label cache,
+ * 1 = no label cache, 2 = 4-bit label cache.  out[0] = launches by the planner's own model of the
+ * device (1: one launch that scores, selects and attends; 2: scoring, then selection behind the
+ * attention; 3: scoring, candidates, attention); out[1] = launches once the occupancy that the
+ * runtime reports for the kernels has been taken into account (-1 when no device is visible);
+ * out[2] = tokens per workgroup, out[3] = workgroups per unit, out[4] = workgroups in the
+ * attention launch, out[5] = compute units planned for, out[6] = 1 if the attention launch
+ * scores as well, out[7] = query heads per KV head.
+ * ds_pretend_device makes the calling thread's plans (and residency checks) assume a device of
+ * `cus` compute units on `xccs` dies with `lds_per_cu` bytes of LDS each, instead of the current
+ * one; (0, 0, 0) ends it.  The workspace layout follows the plan: query ds_workspace_bytes() and
+ * clear the workspace again after switching.  DS_ERR_SHAPE for cus < 1, xccs < 1, cus not a
+ * multiple of xccs, or less than 64 KiB of LDS.
+ */
+ds_status_t ds_plan_describe(const ds_shape_t *shape, int32_t label_kind, int32_t out[8]);
+ds_status_t ds_pretend_device(int32_t cus, int32_t xccs, int32_t lds_per_cu);
 
 #ifdef __cplusplus
 }

@@ -29,7 +29,7 @@ EXPORTS = [
     "ds_append_label_q4", "ds_sparse_decode_q4", "ds_predict_query", "ds_dense_decode", "ds_select",
     "ds_gather_rows_host", "ds_attend_rows", "ds_probe_stream_read", "ds_profile_kernel_count",
     "ds_profile_kernel_name", "ds_profile_enable", "ds_profile_reset", "ds_profile_read",
-    "ds_tune_set", "ds_tune_get",
+    "ds_tune_set", "ds_tune_get", "ds_plan_describe", "ds_pretend_device",
 ]
 
 
@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
                                       ctypes.POINTER(ctypes.c_int64)]
         L.ds_tune_set.argtypes = [ctypes.c_int, ctypes.c_int]
         L.ds_tune_get.argtypes = [ctypes.c_int]
+        L.ds_plan_describe.argtypes = [shp, i32, ctypes.POINTER(ctypes.c_int32)]
+        L.ds_pretend_device.argtypes = [i32, i32, i32]
         for name in EXPORTS:
             getattr(L, name)  # AttributeError names a missing export
         _lib = L
@@ -308,3 +310,15 @@ def ds_tune_set(knob: int, value: int):
 
 def ds_tune_get(knob: int) -> int:
     return lib().ds_tune_get(knob)
+
+
+def ds_plan_describe(shp: DsShape, label_kind: int = 0) -> dict:
+    out = (ctypes.c_int32 * 8)()
+    _check(lib().ds_plan_describe(ctypes.byref(shp), label_kind, out), "ds_plan_describe")
+    keys = ("launches_planned", "launches", "tokens_per_workgroup", "workgroups_per_unit", "workgroups",
+            "compute_units", "scores_itself", "heads_per_kv_head")
+    return dict(zip(keys, list(out)))
+
+
+def ds_pretend_device(cus: int, xccs: int, lds_per_cu: int):
+    _check(lib().ds_pretend_device(cus, xccs, lds_per_cu), "ds_pretend_device")

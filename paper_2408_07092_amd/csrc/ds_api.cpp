@@ -3,6 +3,7 @@
 // No kernel code lives here; every device step is enqueued through the
 // launchers declared in ds_internal.h.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -21,8 +22,50 @@ static __device__ __align__(256) unsigned char scratch[DS_STATIC_SCRATCH_BYTES];
 namespace ds {
 
 // ---------------------------------------------------------------- knobs
-static int g_tune[6] = {0, 0, 0, 0, 0, 0};
-int tune_get(int knob) { return (knob >= 0 && knob < 6) ? g_tune[knob] : 0; }
+// (process-wide, for sweeps and tests; atomic so that a set in one thread and plans made in
+//  another do not race -- a plan reads each knob once)
+static std::atomic<int> g_tune[6];
+int tune_get(int knob) { return (knob >= 0 && knob < 6) ? g_tune[knob].load(std::memory_order_relaxed) : 0; }
+
+// ---------------------------------------------------------------- device
+static thread_local const DeviceCaps *t_pretend = nullptr;
+static thread_local DeviceCaps t_pretend_caps;
+
+void device_caps_pretend(const DeviceCaps *caps)
+{
+    if (caps) {
+        t_pretend_caps = *caps;
+        t_pretend = &t_pretend_caps;
+    } else {
+        t_pretend = nullptr;
+    }
+}
+
+DeviceCaps device_caps()
+{
+    if (t_pretend) return *t_pretend;
+    static std::mutex mu;
+    static DeviceCaps cache[64];
+    static bool have[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();  // no device: the plan of an MI355X
+        return DeviceCaps();
+    }
+    std::lock_guard<std::mutex> lk(mu);
+    if (!have[dev]) {
+        DeviceCaps c;
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) c.cus = v;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeNumberOfXccs, dev) == hipSuccess && v > 0) c.xccs = v;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && v > 0)
+            c.lds_per_cu = v;
+        (void)hipGetLastError();
+        cache[dev] = c;
+        have[dev] = true;
+    }
+    return cache[dev];
+}
 
 // ---------------------------------------------------------------- plans
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -43,29 +86,31 @@ static bool shape_ok(const ds_shape_t &s, bool need_rk)
 // (matrix-core variants, query groups of 3+ heads): LDS is what limits them -- the chunk's keys and
 // row list (6 bytes a token), the chunk histogram or the wavefront partials, whichever is larger,
 // and about 3 KiB of small arrays -- and registers allow three.
-static int group_wgs_per_cu(int G, int ch, int n_ch)
+static int group_wgs_per_cu(int G, int ch, int n_ch, const DeviceCaps &caps)
 {
     const int gt = G <= 4 ? 4 : G <= 8 ? 8 : 16;
     const size_t lds = (size_t)ch * 6 + (size_t)n_ch * 4 + 512 + 3072 +
                        4 * (size_t)std::max(kHistBins, 4 * gt * kPartStride);
-    return (int)std::min<size_t>(3, (160u << 10) / lds);
+    return (int)std::min<size_t>(3, (size_t)caps.lds_per_cu / lds);
 }
 
 bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
 {
     if (!shape_ok(s, true)) return false;
+    const DeviceCaps caps = device_caps();
+    p->cus = caps.cus;
     p->units = s.B * s.Hkv;
     p->G = s.Hq / s.Hkv;
     p->k_eff = std::min(s.k, s.L);
     const int64_t tokens = (int64_t)p->units * s.L;
 
-    int sc = g_tune[0];
+    int sc = tune_get(0);
     // fewer, larger workgroups: every workgroup pays an arrival atomic and a histogram flush
     if (sc == 0) {
         sc = (tokens >= (1 << 21)) ? 4096 : (tokens >= (1 << 20)) ? 2048 : 1024;
         // enough units to fill the device on their own: one workgroup scores a whole short unit
         // and takes the threshold bin from its own histogram, with no traffic between workgroups
-        if (p->units >= 256 && s.L <= 8192) sc = (s.L + 255) & ~255;
+        if (p->units >= caps.cus && s.L <= 8192) sc = (s.L + 255) & ~255;
     }
     p->sc_chunk = sc;
     p->n_sc = (s.L + sc - 1) / sc;
@@ -82,23 +127,23 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
     // what is left refines the threshold in the scoring launch's tail.
     const bool one_wg_units =
         purpose != PLAN_SELECT &&
-        (s.L <= 4096 || (p->units >= 256 && s.L <= 8192) ||
-         (purpose == PLAN_DECODE_SCORING && p->units >= 192 && p->G <= 2 && s.L <= 16384));
+        (s.L <= 4096 || (p->units >= caps.cus && s.L <= 8192) ||
+         (purpose == PLAN_DECODE_SCORING && p->units >= caps.cus * 3 / 4 && p->G <= 2 && s.L <= 16384));
     p->refine_attend = purpose != PLAN_SELECT &&
-                       (g_tune[3] == 4 ||
-                        (g_tune[3] == 0 && (s.L > (1 << 13) || one_wg_units ||
+                       (tune_get(3) == 4 ||
+                        (tune_get(3) == 0 && (s.L > (1 << 13) || one_wg_units ||
                                             (purpose == PLAN_DECODE_SCORING && s.L > (1 << 12)))));
-    int ch = g_tune[1];
+    int ch = tune_get(1);
     p->group_scores_itself = false;
     if (ch == 0 && p->refine_attend && !one_wg_units && p->G > 2 && purpose == PLAN_DECODE_SCORING) {
         // Query groups: one launch that scores as well pays off when all of its workgroups are
         // resident at once (a workgroup waits for the others of its unit twice).  Most
         // workgroups per CU first: the largest number of chunks per unit that still fits.
         for (int w = 3; w >= 1 && ch == 0; --w) {
-            const int n = std::min((256 * w) / p->units, kMaxChunks);
+            const int n = std::min((caps.cus * w) / p->units, kMaxChunks);
             if (n < 1) continue;
             const int c = std::max(2048, (((s.L + n - 1) / n) + 63) & ~63);  // (no point in tiny chunks)
-            if (c <= 8192 && group_wgs_per_cu(p->G, c, (s.L + c - 1) / c) >= w) {
+            if (c <= 8192 && group_wgs_per_cu(p->G, c, (s.L + c - 1) / c, caps) >= w) {
                 ch = c;
                 p->group_scores_itself = true;
             }
@@ -113,10 +158,10 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
         // cores) when chunks of up to 4096 / 6144 tokens allow it
         if (p->G <= 2) {
             ch = 1024;
-            while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 1536) ch *= 2;
+            while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 6 * caps.cus) ch *= 2;
         } else {
             ch = 2048;
-            while (ch < 6144 && ch < s.L && (int64_t)p->units * ((s.L + ch - 1) / ch) > 768) ch += 256;
+            while (ch < 6144 && ch < s.L && (int64_t)p->units * ((s.L + ch - 1) / ch) > 3 * caps.cus) ch += 256;
         }
     } else {
         ch = (tokens >= (1 << 21)) ? 2048 : (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 512 : 256;
@@ -125,7 +170,7 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
         // The matrix-core attention holds three workgroups per CU (768 on the device).  A launch
         // slightly over that runs a nearly empty second round: grow the chunks to fit in one.
         if (p->G >= 4)
-            while ((int64_t)p->units * ((s.L + ch - 1) / ch) > 768 && ch < 6144 && ch < s.L) ch += 256;
+            while ((int64_t)p->units * ((s.L + ch - 1) / ch) > 3 * caps.cus && ch < 6144 && ch < s.L) ch += 256;
     }
     p->ch = ch;
     p->n_ch = (s.L + ch - 1) / ch;
@@ -150,7 +195,7 @@ bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p)
     if (!shape_ok(s, false) || n_tokens < 1) return false;
     p->units = s.B * s.Hkv;
     p->G = s.Hq / s.Hkv;
-    int ch = g_tune[2];
+    int ch = tune_get(2);
     if (ch == 0) {
         const int64_t tokens = (int64_t)p->units * n_tokens;
         ch = (tokens >= (1 << 20)) ? 1024 : (tokens >= (1 << 18)) ? 256 : 64;
@@ -436,6 +481,27 @@ static ds_status_t enqueue_select(const void *q, const void *label, const int32_
     return DS_OK;
 }
 
+static bool label_may_score(const ds_shape_t &s, ScoreSrcKind kind)
+{
+    // the attention launch can score as well when the labels are plain fp16 with 8 or 16 channels,
+    // or 4-bit codes of up to 16 channels in rows that 16-byte loads can take (knob 4 = 1 keeps
+    // the separate scoring launch)
+    return tune_get(4) != 1 && ((kind == SRC_LABEL && (s.r == 8 || s.r == 16)) ||
+                                (kind == SRC_Q4 && s.r <= 16 && (s.L_max & (s.r > 8 ? 1 : 3)) == 0));
+}
+
+// Whether the attention launch of a decode call scores as well: a unit with one workgroup always
+// can; several workgroups per unit wait for each other before all of them have started, so the
+// whole grid has to be resident at once -- single heads and pairs: four workgroups per compute
+// unit; larger query groups: when the plan found chunks that make it so.  Knob 4 = 2 forces it,
+// 1 forbids it.  (The launcher checks the grid against the occupancy the runtime reports.)
+static bool plan_scores_itself(const Plan &p, bool may_score)
+{
+    return may_score && (p.n_ch == 1 || tune_get(4) == 2 ||
+                         (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 4 * (int64_t)p.cus) ||
+                         (tune_get(4) == 0 && p.group_scores_itself));
+}
+
 // ds_sparse_decode with the scores taken from the label cache, from the K rows themselves or from
 // the 4-bit label cache (`label` is then that source's array).
 static ds_status_t sparse_decode_impl(const void *q, const void *label, const void *K, const void *V,
@@ -446,13 +512,7 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
 {
     if (!K || !V || !out) return DS_ERR_NULL;
     Plan p;
-    // the attention launch can score as well when the labels are plain fp16 with 8 or 16 channels,
-    // or 4-bit codes of up to 16 channels in rows that 16-byte loads can take (knob 4 = 1 keeps
-    // the separate scoring launch)
-    const bool may_score =
-        shape && tune_get(4) != 1 &&
-        ((src.kind == SRC_LABEL && (shape->r == 8 || shape->r == 16)) ||
-         (src.kind == SRC_Q4 && shape->r <= 16 && (shape->L_max & (shape->r > 8 ? 1 : 3)) == 0));
+    const bool may_score = shape && label_may_score(*shape, src.kind);
     ds_status_t rc = select_common(q, label, channels, workspace, workspace_bytes, shape, &p,
                                    may_score ? PLAN_DECODE_SCORING : PLAN_DECODE);
     if (rc != DS_OK) return rc;
@@ -467,25 +527,77 @@ static ds_status_t sparse_decode_impl(const void *q, const void *label, const vo
     // threshold bin is published to them) as long as the whole grid is resident at once: single
     // heads and pairs, four workgroups per CU; larger query groups when the plan found chunks that
     // make it so (up to three workgroups per CU).  Knob 4 = 2 forces it, 1 forbids it.
-    const bool scores_itself =
-        may_score && (p.n_ch == 1 || tune_get(4) == 2 ||
-                      (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 1024) ||
-                      (tune_get(4) == 0 && p.group_scores_itself));
+    bool scores_itself = plan_scores_itself(p, may_score);
+    const bool q4 = src.kind == SRC_Q4;
     if (p.refine_attend && refine_attend_ok(p, scores_itself)) {
-        // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
-        // threshold behind the attention over the rows that are selected either way
+        // (the runtime's occupancy figure for the kernel decides whether the workgroups that wait
+        //  for each other are all resident; if not, the separate scoring launch needs less room,
+        //  and the three launches below need none)
+        if (scores_itself && !refine_attend_fits(p, *shape, true, q4)) scores_itself = false;
         if (scores_itself) {
             DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride, label, channels,
-                                        src.kind == SRC_Q4 ? src.amax : nullptr));
+                                        q4 ? src.amax : nullptr));
             return DS_OK;
         }
-        DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, src));
-        DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
-        return DS_OK;
+        // otherwise scoring leaves keys and the threshold bin; one more launch settles the exact
+        // threshold behind the attention over the rows that are selected either way
+        if (refine_attend_ok(p, false) && refine_attend_fits(p, *shape, false, q4)) {
+            DS_TRY(launch_score(q, label, channels, workspace, p, *shape, false, false, st, src));
+            DS_TRY(launch_refine_attend(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
+            return DS_OK;
+        }
     }
     rc = enqueue_select(q, label, channels, workspace, p, *shape, idx_out != nullptr, st, src);
     if (rc != DS_OK) return rc;
     DS_TRY(launch_attend_sparse(q, K, V, workspace, out, idx_out, p, *shape, st, kv_stride));
+    return DS_OK;
+}
+
+ds_status_t ds_pretend_device(int32_t cus, int32_t xccs, int32_t lds_per_cu)
+{
+    if (cus == 0 && xccs == 0 && lds_per_cu == 0) {
+        device_caps_pretend(nullptr);
+        return DS_OK;
+    }
+    if (cus < 1 || xccs < 1 || cus % xccs != 0 || lds_per_cu < (64 << 10)) return DS_ERR_SHAPE;
+    DeviceCaps c;
+    c.cus = cus;
+    c.xccs = xccs;
+    c.lds_per_cu = lds_per_cu;
+    device_caps_pretend(&c);
+    return DS_OK;
+}
+
+ds_status_t ds_plan_describe(const ds_shape_t *shape, int32_t label_kind, int32_t out[8])
+{
+    if (!shape || !out) return DS_ERR_NULL;
+    if (label_kind < 0 || label_kind > 2 || !shape_ok(*shape, true)) return DS_ERR_SHAPE;
+    const ScoreSrcKind kind = static_cast<ScoreSrcKind>(label_kind);
+    const bool may_score = label_may_score(*shape, kind);
+    Plan p;
+    if (!make_plan(*shape, &p, may_score ? PLAN_DECODE_SCORING : PLAN_DECODE)) return DS_ERR_UNSUPPORTED;
+    const bool si = plan_scores_itself(p, may_score);
+    const bool ra = p.refine_attend && refine_attend_ok(p, si);
+    const int planned = !ra ? 3 : si ? 1 : 2;
+    int actual = -1;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+        actual = 3;
+        if (ra) {
+            const bool q4 = kind == SRC_Q4;
+            if (si && refine_attend_fits(p, *shape, true, q4)) actual = 1;
+            else if (refine_attend_ok(p, false) && refine_attend_fits(p, *shape, false, q4)) actual = 2;
+        }
+    }
+    (void)hipGetLastError();
+    out[0] = planned;
+    out[1] = actual;
+    out[2] = p.ch;
+    out[3] = p.n_ch;
+    out[4] = p.units * p.n_ch;
+    out[5] = p.cus;
+    out[6] = si ? 1 : 0;
+    out[7] = p.G;
     return DS_OK;
 }
 
@@ -710,7 +822,7 @@ ds_status_t ds_tune_set(int knob, int value)
         if (knob == 3 && value != 1 && value != 4) return DS_ERR_SHAPE;
         if (knob == 4 && value > 2) return DS_ERR_SHAPE;
     }
-    g_tune[knob] = value;
+    g_tune[knob].store(value, std::memory_order_relaxed);
     return DS_OK;
 }
 

@@ -13,6 +13,9 @@
 // that happens to be.
 // Logits are kept in the log2 domain: s2 = (q.k) * log2(e)/sqrt(d), p = 2^(s2-m).
 #include <algorithm>
+#include <map>
+#include <mutex>
+#include <tuple>
 
 #include "ds_attend_core.h"
 
@@ -245,6 +248,30 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     uint2 *ready = reinterpret_cast<uint2 *>(&ctl->cnt_a);  // {T, tie cut | 1<<31}
     unsigned long long *cand_arrive = reinterpret_cast<unsigned long long *>(&ctl->pad[2]);
     DS_TR(0);
+    // A wait for another workgroup that ran out: the unit's error word is raised (it stays up until
+    // the workspace is cleared) and the workgroup remembers it for its last arrival, so that the
+    // workgroup that would merge the unit writes NaN instead.  A unit whose word is up when the
+    // launch starts is not computed at all: its output is NaN again.
+    __shared__ uint32_t s_failed;
+    auto raise_err = [&](uint32_t code) {
+        st_dev(&ctl->err, code);
+        s_failed = 1u;
+    };
+    auto poison_out = [&]() {
+        float *ou = a.out + (size_t)u * a.G * kD;
+        for (int i = tid; i < a.G * kD; i += WGT) ou[i] = __builtin_nanf("");
+    };
+    // (the word is asked for here and looked at after the chunk has been scored, before the first
+    //  thing that another workgroup could see: the load is off the path)
+    const uint32_t sticky = a.ctl[u].err;
+    auto refuse_if_poisoned = [&]() {
+        if (sticky != 0u && c == 0) poison_out();
+        return sticky != 0u;
+    };
+    if (tid == 0) s_failed = 0u;
+    if constexpr (SMODE == 0) {
+        if (refuse_if_poisoned()) return;
+    }
 
     uint32_t bstar = kHistBins - 1, krem_unit = 1;
     if constexpr (SMODE != 0) {
@@ -375,6 +402,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         }
         }  // fp16 labels
         DS_PRIO(3);
+        if (refuse_if_poisoned()) return;
         __syncthreads();
         DS_TR(11);
         if (gridDim.x == 1) {
@@ -430,7 +458,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                         }
                     }
                     s_ok = ok;
-                    if (!ok) st_dev(&ctl->err, 9u);
+                    if (!ok) raise_err(9u);
                 }
                 __syncthreads();
                 DS_TR(12);
@@ -520,7 +548,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                     s_T[0] = ok ? w.x : (uint32_t)(kHistBins - 1);
                     s_T[1] = ok ? (w.y & 0x7fffffffu) : 1u;
                     s_ok = ok;
-                    if (!ok) st_dev(&ctl->err, 9u);
+                    if (!ok) raise_err(9u);
                 }
             }
             __syncthreads();
@@ -674,7 +702,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
             }
         } else if (tid == 0) {
-            st_dev(&ctl->err, 8u);
+            raise_err(8u);
         }
     }
     DS_TR(1);
@@ -838,7 +866,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 s_T[0] = w.x;
                 s_T[1] = w.y & 0x7fffffffu;
                 s_ok = ok;
-                if (!ok) st_dev(&ctl->err, 6u);
+                if (!ok) raise_err(6u);
             }
             __syncthreads();
             T = s_T[0];
@@ -960,18 +988,33 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     // ---- last workgroup of the unit: merge the chunk partials, leave the control words clean
     if (single) return;
     {
-        const bool last = last_arrival(&ctl->arrive_c, gridDim.x, &s_flag);
+        // (the arrival count in the low half of the word; a workgroup whose wait ran out adds a
+        //  mark in the high half, which the last one to arrive sees without another load)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t mine = s_failed ? 0x10000u : 0u;
+            const uint32_t t = __hip_atomic_fetch_add(&ctl->arrive_c, 1u + mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_flag = ((t & 0xffffu) == gridDim.x - 1u) ? 1u : 0u;
+            s_ok = ((t >> 16) != 0u || mine != 0u) ? 0u : 1u;
+        }
+        __syncthreads();
         DS_TR(6);
-        if (!last) return;
+        if (!s_flag) return;
     }
+    const bool unit_ok = s_ok != 0u;
     if (tid == 0) {
         ctl->arrive_c = 0u;
         ctl->cnt_a = 0u;
         ctl->cnt_b = 0u;
     }
-    if constexpr (NW == 4)  // (written for 256 threads; the wider variant never gets here)
+    if (!unit_ok) {
+        poison_out();
+    } else if constexpr (NW == 4) {  // (written for 256 threads; the wider variant never gets here)
         merge_partials(a.part + (size_t)u * a.G * a.n_ch * kPartStride, a.G, a.n_ch,
                        a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
+    }
     DS_TR(7);
     if constexpr (SMODE != 0 && kAllFind && NW == 4) {
         // every workgroup of the unit has long read the unit's histograms and passed their arrival
@@ -1031,29 +1074,126 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
     return hipGetLastError();
 }
 
-// Whether k_refine_attend can take this plan: chunks of at most 6144 tokens (six
-// passes of four keys per thread, 16-bit row offsets), and room on one XCD for its
-// share (every eighth workgroup) of a unit's n_ch workgroups at a time.
+// Whether k_refine_attend can take this plan's chunks: keys loaded from memory come in at most
+// eight passes of 1024; a workgroup that scores its unit itself writes them to LDS directly
+// (16-bit row offsets: up to 16384 tokens).
 bool refine_attend_ok(const Plan &p, bool scores_itself)
 {
-    // keys loaded from memory come in at most eight passes of 1024; a workgroup that scores its
-    // unit itself writes them to LDS directly (16-bit row offsets: up to 16384 tokens tried)
-    if (p.ch > (scores_itself ? 16384 : 8192) || (p.ch & 3)) return false;
-    static int per_xcd = 0;
-    if (!per_xcd) {
-        hipDeviceProp_t prop;
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
-        per_xcd = std::max(1, prop.multiProcessorCount / 8);  // one resident workgroup per CU at least
+    return p.ch <= (scores_itself ? 16384 : 8192) && (p.ch & 3) == 0;
+}
+
+// ---- the instantiation that serves a launch, by function pointer
+using RaFn = void (*)(AttendArgs);
+struct RaKernel {
+    RaFn fn;
+    int threads;
+};
+
+// smode: 0 = keys and threshold bin come from the scoring launch; 8 / 16 = fp16 labels of that
+// many channels scored here; -8 / -16 = 4-bit labels of up to that many channels scored here.
+template <int GT, int RPS>
+static RaFn ra_fn(int smode)
+{
+    switch (smode) {
+    case 0: return RPS > 4 ? nullptr : static_cast<RaFn>(k_refine_attend<GT, 0, 4>);
+    case 8: return k_refine_attend<GT, 8, RPS>;
+    case 16: return k_refine_attend<GT, 16, RPS>;
+    case -8: return k_refine_attend<GT, -8, RPS>;
+    default: return k_refine_attend<GT, -16, RPS>;
     }
-    return (p.n_ch + 7) / 8 <= per_xcd;
+}
+
+static size_t ra_shmem(const Plan &p) { return (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4; }
+
+static RaKernel ra_kernel(const Plan &p, int smode)
+{
+    const int gt = pick_gt(p.G);
+    // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot in flight
+    if (smode && gt == 1 && ra_shmem(p) > (64u << 10) && p.n_ch == 1) return {ra_fn<1, 8>(smode), 1024};
+    switch (gt) {
+    case 16: return {ra_fn<16, DS_MC_RPS>(smode), 256};
+    case 8: return {ra_fn<8, DS_MC_RPS>(smode), 256};
+    case 4: return {ra_fn<4, DS_MC_RPS>(smode), 256};
+    case 2: return {ra_fn<2, DS_MC_RPS>(smode), 256};
+    default: return {ra_fn<1, DS_MC_RPS>(smode), 256};
+    }
+}
+
+// 0 when the labels cannot be scored in the attention launch
+static int ra_smode(const ds_shape_t &s, bool scores_itself, bool q4)
+{
+    if (!scores_itself) return 0;
+    if (q4) return (s.r > 16 || (s.L_max & (s.r > 8 ? 1 : 3))) ? 0 : (s.r > 8 ? -16 : -8);
+    return (s.r == 8 || s.r == 16) ? s.r : 0;
+}
+
+// What the runtime says of a kernel, asked once per (kernel, dynamic LDS): more than 64 KiB of
+// dynamic LDS has to be granted first (all that the compute unit has beyond the kernel's static
+// arrays); then the number of its workgroups that one compute unit holds at a time.
+static int ra_workgroups_per_cu(const RaKernel &k, size_t shmem, const DeviceCaps &caps)
+{
+    struct Key {
+        const void *fn;
+        size_t shmem;
+        int dev;
+        bool operator<(const Key &o) const { return std::tie(fn, shmem, dev) < std::tie(o.fn, o.shmem, o.dev); }
+    };
+    static std::mutex mu;
+    static std::map<Key, int> cache;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    const void *fn = reinterpret_cast<const void *>(k.fn);
+    std::lock_guard<std::mutex> lk(mu);
+    const Key key{fn, shmem, dev};
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
+    int per_cu = 0;
+    bool ok = true;
+    if (shmem > (64u << 10)) {
+        hipFuncAttributes fa;
+        ok = hipFuncGetAttributes(&fa, fn) == hipSuccess;
+        const int room = ok ? caps.lds_per_cu - (int)fa.sharedSizeBytes : 0;
+        ok = ok && (size_t)room >= shmem &&
+             hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, room) == hipSuccess;
+    }
+    if (ok && hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, k.threads, shmem) != hipSuccess) per_cu = 0;
+    if (!ok) per_cu = 0;
+    (void)hipGetLastError();
+    cache[key] = per_cu;
+    return per_cu;
+}
+
+// Whether the device holds, at the same time, all the workgroups that a launch of this plan lets
+// wait for each other.  A launch that scores as well waits (for its unit's histogram) for
+// workgroups that may not have started: the whole grid has to be resident.  After a scoring
+// launch a workgroup waits only for one that is running; workgroups start in grid order and are
+// dealt out to the dies in turn, so one die has to hold its share of a unit's workgroups.  A unit
+// with a single workgroup waits for nobody.
+static bool ra_fits(const RaKernel &k, const Plan &p, int smode)
+{
+    if (!k.fn) return false;
+    const DeviceCaps caps = device_caps();
+    const int per_cu = ra_workgroups_per_cu(k, ra_shmem(p), caps);
+    if (per_cu < 1) return false;
+    if (p.n_ch == 1) return true;
+    if (smode != 0) return (int64_t)p.n_ch * p.units <= (int64_t)per_cu * caps.cus;
+    const int dies = std::max(1, caps.xccs);
+    return (p.n_ch + dies - 1) / dies <= per_cu * std::max(1, caps.cus / dies);
+}
+
+bool refine_attend_fits(const Plan &p, const ds_shape_t &s, bool scores_itself, bool q4)
+{
+    const int smode = ra_smode(s, scores_itself, q4);
+    if (scores_itself && smode == 0) return false;
+    return ra_fits(ra_kernel(p, smode), p, smode);
 }
 
 // score_label / score_channels: non-null to run the scoring in the same launch (fp16 labels of 8
 // or 16 channels; with score_amax the 4-bit label cache of up to 16 channels, whose token rows
 // must be 16-byte loadable: L_max % 4 == 0 for one word per token, L_max % 2 == 0 for two);
 // otherwise the keys and the threshold bin of a preceding k_score launch are read from the
-// workspace.
+// workspace.  kNotResident, with nothing enqueued, when the device cannot hold the workgroups
+// that would wait for each other.
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
                                 int kv_stride, const void *score_label, const int32_t *score_channels,
@@ -1083,69 +1223,17 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.coarse = reinterpret_cast<uint32_t *>(wsp(ws, p.off_coarse));
     a.amax = score_amax;
     a.r = s.r;
-    int smode = 0;
-    if (score_label && score_amax) {
-        if (s.r > 16 || (s.L_max & (s.r > 8 ? 1 : 3))) return hipErrorInvalidValue;
-        smode = s.r > 8 ? -16 : -8;
-    } else if (score_label) {
-        if (s.r != 8 && s.r != 16) return hipErrorInvalidValue;
-        smode = s.r;
-    }
-    const size_t shmem = (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4;
-    const dim3 grid(p.n_ch, p.units);
-    // more than 64 KiB of dynamic LDS has to be asked for once per kernel: all that the CU has
-    // (160 KiB) beyond the kernel's static arrays
-#define DS_RA_ATTR(KERNEL)                                                                             \
-    do {                                                                                               \
-        static int max_dyn = 0;                                                                        \
-        if (shmem > (64u << 10) && !max_dyn) {                                                         \
-            hipFuncAttributes fa;                                                                      \
-            if (hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&KERNEL)) != hipSuccess)      \
-                return hipErrorInvalidValue;                                                           \
-            const int room = (160 << 10) - (int)fa.sharedSizeBytes;                                    \
-            if (room < (64 << 10) ||                                                                   \
-                hipFuncSetAttribute(reinterpret_cast<const void *>(&KERNEL),                           \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, room) != hipSuccess)   \
-                return hipErrorInvalidValue;                                                           \
-            max_dyn = room;                                                                            \
-        }                                                                                              \
-        if (shmem > (64u << 10) && shmem > (size_t)max_dyn) return hipErrorInvalidValue;               \
-    } while (0)
-#define DS_RA_ONE(GTV, SM, RPSV)                                                                       \
-    do {                                                                                               \
-        DS_RA_ATTR((k_refine_attend<GTV, SM, RPSV>));                                                   \
-        DS_LAUNCH(KID_REFINE_ATTEND, (k_refine_attend<GTV, SM, RPSV>), grid, dim3((RPSV) > 4 ? 1024 : 256), shmem, st, a); \
-    } while (0)
-#define DS_RA_SM(GTV, RPSV)                                                                            \
-    do {                                                                                               \
-        if (smode == 8) DS_RA_ONE(GTV, 8, RPSV);                                                        \
-        else if (smode == 16) DS_RA_ONE(GTV, 16, RPSV);                                                 \
-        else if (smode == -8) DS_RA_ONE(GTV, -8, RPSV);                                                 \
-        else DS_RA_ONE(GTV, -16, RPSV);                                                                 \
-    } while (0)
-#define DS_RA(GTV)                                                                                     \
-    do {                                                                                               \
-        if (smode == 0) DS_RA_ONE(GTV, 0, DS_MC_RPS);                                                   \
-        else DS_RA_SM(GTV, DS_MC_RPS);                                                                       \
-    } while (0)
-    if (smode && pick_gt(a.G) == 1 && shmem > (64u << 10) && p.n_ch == 1) {
-        // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot
-        // in flight
-        DS_RA_SM(1, 8);
-        return hipGetLastError();
-    }
-    switch (pick_gt(a.G)) {
-    case 16: DS_RA(16); break;
-    case 8: DS_RA(8); break;
-    case 4: DS_RA(4); break;
-    case 2: DS_RA(2); break;
-    default: DS_RA(1); break;
-    }
-#undef DS_RA
-#undef DS_RA_SM
-#undef DS_RA_ONE
-#undef DS_RA_ATTR
-    return hipGetLastError();
+    const int smode = ra_smode(s, score_label != nullptr, score_amax != nullptr);
+    if (score_label && smode == 0) return hipErrorInvalidValue;
+    const RaKernel k = ra_kernel(p, smode);
+    if (!k.fn) return hipErrorInvalidValue;
+    if (!ra_fits(k, p, smode)) return kNotResident;
+    const dim3 grid(p.n_ch, p.units), block(k.threads);
+    void *args[] = {&a};
+    hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    if (prof_events(KID_REFINE_ATTEND, &ev_a, &ev_b))
+        return hipExtLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st, ev_a, ev_b, 0);
+    return hipLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st);
 }
 
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,

@@ -61,6 +61,7 @@ enum KernelId {
 // Launch plan of one sparse decode / select call and its workspace layout.
 struct Plan {
     int units, G, k_eff;
+    int cus;             // compute units of the device the plan was made for
     int sc_chunk, n_sc;  // tokens per workgroup / workgroups per unit, scoring
     int ch, n_ch;        // same for candidate collection, compaction and attention
     int key_stride;      // uint32 keys per unit (L rounded up to 4)
@@ -83,6 +84,15 @@ struct ScoreSrc {
     ScoreSrcKind kind = SRC_LABEL;
     const float *amax = nullptr;  // SRC_Q4: [units][r]
 };
+
+// What the launch plans need to know of the device: compute units, the dies (XCDs) that workgroups
+// are dealt out to in turn, and LDS bytes per compute unit.  Taken from the current device, or the
+// figures of an MI355X when no device is visible (a plan made on a host without one).
+struct DeviceCaps {
+    int cus = 256, xccs = 8, lds_per_cu = 160 << 10;
+};
+DeviceCaps device_caps();                  // of the current device (cached per device)
+void device_caps_pretend(const DeviceCaps *caps);  // test hook: overrides device_caps() for this thread (nullptr: off)
 
 // What the plan is for: the split select call (and anything that runs the candidate launch), a
 // decode call, or a decode call whose single workgroup per unit may do the scoring itself.
@@ -107,6 +117,10 @@ hipError_t launch_attend_sparse(const void *q, const void *K, const void *V, voi
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s,
                                 hipStream_t st, int kv_stride = kD);
 bool refine_attend_ok(const Plan &p, bool scores_itself);
+// Returned by launch_refine_attend (nothing enqueued) when the launch would wait for workgroups
+// that the device cannot hold at the same time as the waiting ones.
+constexpr hipError_t kNotResident = hipErrorLaunchOutOfResources;
+bool refine_attend_fits(const Plan &p, const ds_shape_t &s, bool scores_itself, bool q4);
 hipError_t launch_refine_attend(const void *q, const void *K, const void *V, void *ws, float *out,
                                 int32_t *idx_out, const Plan &p, const ds_shape_t &s, hipStream_t st,
                                 int kv_stride = kD, const void *score_label = nullptr,

@@ -143,3 +143,38 @@ def test_calibrate_tie_rule_and_small_values():
     assert ds.ds_calibrate_channels(qc, kc, 3, ds.DS_CALIB_QK).tolist() == [[1, 4, 5]]
     assert ds.ds_calibrate_channels(qc, kc, 2, ds.DS_CALIB_K).tolist() == [[0, 1]]
     assert np.array_equal(ds.ds_calibrate_channels(qc, kc, 3, 0), O.calibrate(qc, kc, 3, 0)[0])
+
+
+def test_planner_follows_the_device_it_is_told_of():
+    """Host only: the launch plan is derived from the device's compute-unit count, not from
+    literals.  On the default device model (256 compute units) the headline shapes decode in one
+    launch whose workgroups all fit at once; told of a device a quarter the size, the planner
+    must not plan a launch whose workgroups wait for others that cannot be resident."""
+    shapes = {"C3": ds.shape(1, 32, 32, 128, 65536, 65536, 8, 4096),
+              "C4a": ds.shape(16, 64, 8, 128, 32768, 32768, 8, 2048)}
+    for name, shp in shapes.items():
+        ds.ds_pretend_device(256, 8, 160 << 10)
+        try:
+            big = ds.ds_plan_describe(shp)
+            ds.ds_pretend_device(64, 8, 160 << 10)
+            small = ds.ds_plan_describe(shp)
+            ws_small = ds.ds_workspace_bytes(shp)
+        finally:
+            ds.ds_pretend_device(0, 0, 0)
+        assert big["compute_units"] == 256 and small["compute_units"] == 64
+        assert big["launches_planned"] == 1 and big["scores_itself"] == 1, (name, big)
+        per_cu = 4 if big["heads_per_kv_head"] <= 2 else 3
+        assert big["workgroups"] <= per_cu * 256, (name, big)
+        assert small["launches_planned"] >= 2 and small["scores_itself"] == 0, (name, small)
+        assert ws_small > 0
+    # one workgroup per unit waits for nobody: the same plan on any device
+    c1 = ds.shape(1, 32, 32, 128, 4096, 4096, 8, 256)
+    ds.ds_pretend_device(16, 8, 160 << 10)
+    try:
+        assert ds.ds_plan_describe(c1)["launches_planned"] == 1
+    finally:
+        ds.ds_pretend_device(0, 0, 0)
+    # the hook refuses devices that cannot exist
+    for bad in ((0, 8, 160 << 10), (100, 8, 160 << 10), (64, 8, 1024)):
+        with pytest.raises(ds.DsError):
+            ds.ds_pretend_device(*bad)

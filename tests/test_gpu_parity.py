@@ -681,7 +681,7 @@ def test_waits_that_give_up_end_the_launch_and_are_reported(decode_path):
     assert ds.ds_workspace_errors(case.ws, case.shape) == (0, 0)
     ds.ds_tune_set(5, 1)
     try:
-        case.gpu_sparse()                      # must return; what it computed does not matter
+        bad, _ = case.gpu_sparse()             # must return
         n_failed, code = ds.ds_workspace_errors(case.ws, case.shape)
     finally:
         ds.ds_tune_set(5, 0)
@@ -691,10 +691,52 @@ def test_waits_that_give_up_end_the_launch_and_are_reported(decode_path):
     assert n_failed <= Hkv and code in (0, 6, 9)
     if decode_path != "refine_attend":
         assert n_failed > 0
+    # a unit whose wait ran out is all NaN, never a wrong number; the others are right
+    nan_units = np.isnan(bad).all(axis=-1)[0]
+    assert int(nan_units.sum()) == n_failed
+    assert not np.isnan(bad[0][~nan_units]).any()
+    assert bad[0][~nan_units].tobytes() == good[0][~nan_units].tobytes()
+    # the error words stay up: the next call on the workspace gives NaN for those units again
+    if n_failed:
+        bad2, _ = case.gpu_sparse()
+        assert (np.isnan(bad2).all(axis=-1)[0] == nan_units).all()
+        assert ds.ds_workspace_errors(case.ws, case.shape)[0] == n_failed
     ds.ds_workspace_init(case.ws)
     again, idx2 = case.gpu_sparse()
     assert ds.ds_workspace_errors(case.ws, case.shape) == (0, 0)
     assert again.tobytes() == good.tobytes() and np.array_equal(idx, idx2)
+
+
+def test_grid_that_is_not_resident_takes_more_launches(decode_path):
+    """The planner is told of a device a quarter the size: the one-launch shape, whose workgroups
+    wait for each other, no longer fits at once, and the call must take launch shapes that need
+    less room -- and give the same bytes as on the real device."""
+    if decode_path != "auto":
+        pytest.skip("default launch shape only")
+    L, k, Hkv = 40000, 2500, 8
+    rng = np.random.default_rng(12)
+    q = rng.standard_normal((2, Hkv, 128)).astype(np.float16)
+    K = rng.standard_normal((2, Hkv, L, 128)).astype(np.float16)
+    V = rng.standard_normal((2, Hkv, L, 128)).astype(np.float16)
+    case = Case(q, K, V, rand_channels(Hkv, 128, 8, seed=3), L, k)
+    case.gpu_build_label()
+    good, idx = case.gpu_sparse()
+    plan_real = ds.ds_plan_describe(case.shape, 2)
+    ds.ds_profile_reset(); ds.ds_profile_enable(True)
+    try:
+        ds.ds_pretend_device(8, 8, 160 << 10)      # 8 compute units: 640 workgroups cannot be resident
+        plan_small = ds.ds_plan_describe(case.shape, 2)
+        case.ws = ds.ds_workspace_alloc(case.shape)
+        small, idx_s = case.gpu_sparse()
+        launched = ds.ds_profile_read()
+    finally:
+        ds.ds_pretend_device(0, 0, 0)
+        ds.ds_profile_enable(False); ds.ds_profile_reset()
+    assert plan_real["launches"] == 1 and plan_small["launches"] > 1, (plan_real, plan_small)
+    assert "k_score" in launched, launched
+    assert ds.ds_workspace_errors(case.ws, case.shape) == (0, 0)
+    assert np.array_equal(idx_s, idx)
+    check_output(small, good.astype(np.float64), "pretended small device")
 
 
 # ---------------------------------------------------------------- determinism across processes

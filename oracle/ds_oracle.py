@@ -16,23 +16,36 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ds_oracle.c")
 _LIB = os.path.join(_HERE, "libds_oracle.so")
+# The same source under AddressSanitizer and UndefinedBehaviorSanitizer (host code only).  A
+# process that sets DS_ORACLE_SANITIZE=1 loads this build; it has to be started with the ASan
+# runtime preloaded (see tests/test_oracle_pins.py::test_pins_hold_under_sanitizers).
+_LIB_SAN = os.path.join(_HERE, "libds_oracle_san.so")
+SANITIZE = os.environ.get("DS_ORACLE_SANITIZE", "") == "1"
 _lib = None
 
 
-def build(force: bool = False) -> str:
+def build(force: bool = False, sanitize: bool = False) -> str:
     """Compile ds_oracle.c with gcc (fp contraction off, OpenMP over units)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC",
-               "-shared", "-o", _LIB, _SRC, "-lm"]
+    lib = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+               "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+        cmd = ["gcc"] + opt + ["-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC",
+                               "-shared", "-o", lib, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
+
+
+def asan_runtime() -> str:
+    """Path of gcc's ASan runtime, to be preloaded by a process that loads the sanitized build."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
 
 
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        _lib = ctypes.CDLL(build(sanitize=SANITIZE))
     return _lib
 
 

@@ -31,6 +31,34 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+GUARD = 256  # bytes of canary on either side of a guarded buffer
+
+
+class Guarded:
+    """A device buffer between two canary bands: `view` is what the library gets; check()
+    asserts that nothing was written outside it."""
+
+    def __init__(self, nbytes, dtype, shape=None, fill=None):
+        self.raw = torch.full((nbytes + 2 * GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+        inner = self.raw[GUARD:GUARD + nbytes]
+        self.view = inner.view(dtype) if shape is None else inner.view(dtype).view(shape)
+        if fill is not None:
+            self.view.fill_(fill)
+
+    def check(self, what):
+        lo, hi = self.raw[:GUARD], self.raw[-GUARD:]
+        assert bool((lo == 0xA5).all()) and bool((hi == 0xA5).all()), f"{what}: written outside the buffer"
+
+
+def guarded_workspace(shape):
+    """Cleared workspace of exactly ds_workspace_bytes() between canary bands."""
+    n = ds.ds_workspace_bytes(shape)
+    g = Guarded(n, torch.uint8)
+    ds.ds_workspace_init(g.view)
+    torch.cuda.synchronize()
+    return g
+
+
 class Case:
     """Device tensors + shape for one layer; host copies for the oracle."""
 
@@ -44,7 +72,8 @@ class Case:
         self.ch = to_dev(self.ch_h)
         self.shape = ds.shape(self.B, self.Hq, self.Hkv, self.d, L, self.L_max, self.r, k)
         self.label = torch.zeros((self.B, self.Hkv, self.L_max, self.r), dtype=torch.float16, device="cuda")
-        self.ws = ds.ds_workspace_alloc(self.shape)
+        self._ws_guard = guarded_workspace(self.shape)
+        self.ws = self._ws_guard.view
 
     @classmethod
     def from_torch(cls, t, channels, L, k):
@@ -59,7 +88,8 @@ class Case:
         self.ch = to_dev(self.ch_h)
         self.shape = ds.shape(self.B, self.Hq, self.Hkv, self.d, L, self.L_max, self.r, k)
         self.label = torch.zeros((self.B, self.Hkv, self.L_max, self.r), dtype=torch.float16, device="cuda")
-        self.ws = ds.ds_workspace_alloc(self.shape)
+        self._ws_guard = guarded_workspace(self.shape)
+        self.ws = self._ws_guard.view
         return self
 
     # ---- HIP path
@@ -68,31 +98,43 @@ class Case:
         torch.cuda.synchronize()
         return self.label.cpu().numpy()
 
-    def gpu_sparse(self, want_idx=True):
-        out = torch.full((self.B, self.Hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
-        idx = torch.full((self.B, self.Hkv, self.k), -7, dtype=torch.int32, device="cuda") if want_idx else None
-        ds.ds_sparse_decode(self.q, self.label, self.K, self.V, self.ch, out, idx, self.ws, self.shape)
+    def _outputs(self, want_idx=True):
+        """Output and index buffers between canary bands, pre-filled with values no call writes."""
+        out = Guarded(self.B * self.Hq * self.d * 4, torch.float32, (self.B, self.Hq, self.d), float("nan"))
+        idx = Guarded(self.B * self.Hkv * self.k * 4, torch.int32, (self.B, self.Hkv, self.k), -7) if want_idx else None
+        return out, idx
+
+    def _checked(self, out, idx, what):
+        """After a call: nothing outside the output, the index list or the workspace was written
+        (the workspace guard only when the call ran on the case's own workspace)."""
         torch.cuda.synchronize()
-        return out.cpu().numpy(), (idx.cpu().numpy() if want_idx else None)
+        out.check(what + " out")
+        if idx is not None:
+            idx.check(what + " idx_out")
+        if self.ws.data_ptr() == self._ws_guard.view.data_ptr():
+            self._ws_guard.check(what + " workspace")
+        return out.view.cpu().numpy(), (idx.view.cpu().numpy() if idx is not None else None)
+
+    def gpu_sparse(self, want_idx=True):
+        out, idx = self._outputs(want_idx)
+        ds.ds_sparse_decode(self.q, self.label, self.K, self.V, self.ch, out.view, idx.view if idx else None, self.ws,
+                            self.shape)
+        return self._checked(out, idx, "ds_sparse_decode")
 
     def gpu_sparse_nolabel(self):
-        out = torch.full((self.B, self.Hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
-        idx = torch.full((self.B, self.Hkv, self.k), -7, dtype=torch.int32, device="cuda")
-        ds.ds_sparse_decode_nolabel(self.q, self.K, self.V, self.ch, out, idx, self.ws, self.shape)
-        torch.cuda.synchronize()
-        return out.cpu().numpy(), idx.cpu().numpy()
+        out, idx = self._outputs()
+        ds.ds_sparse_decode_nolabel(self.q, self.K, self.V, self.ch, out.view, idx.view, self.ws, self.shape)
+        return self._checked(out, idx, "ds_sparse_decode_nolabel")
 
     def gpu_dense(self):
-        out = torch.full((self.B, self.Hq, self.d), float("nan"), dtype=torch.float32, device="cuda")
-        ds.ds_dense_decode(self.q, self.K, self.V, out, self.ws, self.shape)
-        torch.cuda.synchronize()
-        return out.cpu().numpy()
+        out, _ = self._outputs(False)
+        ds.ds_dense_decode(self.q, self.K, self.V, out.view, self.ws, self.shape)
+        return self._checked(out, None, "ds_dense_decode")[0]
 
     def gpu_select(self):
-        idx = torch.full((self.B, self.Hkv, self.k), -7, dtype=torch.int32, device="cuda")
-        ds.ds_select(self.q, self.label, self.ch, idx, self.ws, self.shape)
-        torch.cuda.synchronize()
-        return idx.cpu().numpy()
+        out, idx = self._outputs()
+        ds.ds_select(self.q, self.label, self.ch, idx.view, self.ws, self.shape)
+        return self._checked(out, idx, "ds_select")[1]
 
     # ---- oracle
     def oracle_label(self):
@@ -154,6 +196,20 @@ def check_index_band(idx_gpu, scores64, sorted64, L, k):
                     assert abs(tau - nxt) <= BAND * max(abs(tau), abs(nxt)), \
                         f"unit ({b},{h}): sets differ although the k-th and (k+1)-th scores are separated"
     return differing
+
+
+def check_decode_against_both_oracles(idx_gpu, out_gpu, q, label, K, V, ch, L, k, what=""):
+    """Index list and output of one decode against the oracle in both of its modes: identical
+    to the selection on binary32 scores in the library's stated order, identical to the float64
+    definition except inside the near-tie band, output within the bar of the float64 oracle
+    (evaluated on the library's set if that differs inside the band)."""
+    check_index_structure(idx_gpu, L, k)
+    _, idx32 = O.sparse_decode(q, label, K, V, ch, L, k, precision=32)
+    assert np.array_equal(idx_gpu, idx32), f"{what}: index sets differ from the binary32-order oracle"
+    out64, _, sc64, srt64 = O.sparse_decode(q, label, K, V, ch, L, k, precision=64, want_scores=True)
+    differing = check_index_band(idx_gpu, sc64, srt64, L, k)
+    ref = out64 if differing == 0 else O.attend_idx(q, K, V, idx_gpu)
+    return check_output(out_gpu, ref, what)
 
 
 def full_parity(case: Case, check_dense=True, what=""):

@@ -10,7 +10,8 @@ import torch
 
 import paper_2408_07092_amd as ds
 from oracle import ds_oracle as O
-from tests.parity_util import Case, check_index_band, check_index_structure, check_output, full_parity, to_dev
+from tests.parity_util import (Case, check_decode_against_both_oracles, check_index_band, check_index_structure,
+                               check_output, full_parity, to_dev)
 from workloads import (WORKLOADS, Workload, make_calibration_numpy, make_layer_numpy, make_layer_torch,
                        outlier_channels)
 
@@ -267,12 +268,11 @@ def test_select_gather_from_pinned_host_attend_rows():
     ds.ds_attend_rows(case.q, rows, out, case.ws, case.shape)
     torch.cuda.synchronize()
     idx_h, rows_h = idx.cpu().numpy(), rows.cpu().numpy()
-    ref_out, ref_idx = O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, 3000, 200, precision=32)
-    assert np.array_equal(idx_h, ref_idx)
+    check_decode_against_both_oracles(idx_h, out.cpu().numpy(), t["q"], lab_ref, t["K"], t["V"], ch, 3000, 200,
+                                      "offload split path")
     for h in range(4):
         assert np.array_equal(rows_h[0, h, :, 0].view(np.uint16), t["K"][0, h, idx_h[0, h]].view(np.uint16))
         assert np.array_equal(rows_h[0, h, :, 1].view(np.uint16), t["V"][0, h, idx_h[0, h]].view(np.uint16))
-    check_output(out.cpu().numpy(), ref_out, "offload split path")
 
 
 def test_offload_pipeline_double_buffer_matches_oracle_over_layers():
@@ -286,7 +286,13 @@ def test_offload_pipeline_double_buffer_matches_oracle_over_layers():
         t = make_layer_numpy(w, layer=l)
         ch = rand_channels(w.Hkv, 128, 8, 100 + l)
         lab_ref = O.build_label(t["K"], ch, w.L)
-        refs.append(O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, w.L, w.k, precision=32)[0])
+        # the pipeline hands back outputs only: the reference is the float64 definition, on the
+        # binary32-order selection (which the band check ties to the float64 one) where they differ
+        _, idx32 = O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, w.L, w.k, precision=32)
+        out64, _, sc64, srt64 = O.sparse_decode(t["q"], lab_ref, t["K"], t["V"], ch, w.L, w.k, precision=64,
+                                                want_scores=True)
+        differing = check_index_band(idx32, sc64, srt64, w.L, w.k)
+        refs.append(out64 if differing == 0 else O.attend_idx(t["q"], t["K"], t["V"], idx32))
         layers.append((to_dev(t["q"]), to_dev(lab_ref), to_dev(ch),
                        torch.from_numpy(t["K"]).pin_memory(), torch.from_numpy(t["V"]).pin_memory()))
         outs.append(torch.zeros((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda"))
@@ -404,11 +410,8 @@ def test_full_config_c5_offload_rows_from_pinned_host():
     ds.ds_gather_rows_host(Kp, Vp, idx, rows, shp)
     ds.ds_attend_rows(t["q"], rows, out, ws, shp)
     torch.cuda.synchronize()
-    ref_out, ref_idx = O.sparse_decode(q_h, lab_ref, K_h, V_h, ch, w.L, w.k, precision=32)
-    idx_h = idx.cpu().numpy()
-    check_index_structure(idx_h, w.L, w.k)
-    assert np.array_equal(idx_h, ref_idx)
-    print("C5", check_output(out.cpu().numpy(), ref_out, "C5 offload"))
+    print("C5", check_decode_against_both_oracles(idx.cpu().numpy(), out.cpu().numpy(), q_h, lab_ref, K_h, V_h, ch,
+                                                  w.L, w.k, "C5 offload"))
 
 
 def test_nolabel_rejects_bad_arguments_and_matches_label_path_bytes():
@@ -487,10 +490,8 @@ def test_interleaved_cache_append_and_decode(B, Hq, Hkv, L, L_max, r, k):
     idx = torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda")
     ds.ds_sparse_decode_kv(to_dev(q), lab_i, KV_d, ch_d, out, idx, ws, shp)
     torch.cuda.synchronize()
-    ref_out, ref_idx = O.sparse_decode(q, lab_o, K_o, V_o, ch, L, k, precision=32)
-    check_index_structure(idx.cpu().numpy(), L, k)
-    assert np.array_equal(idx.cpu().numpy(), ref_idx)
-    check_output(out.cpu().numpy(), ref_out, "interleaved decode")
+    check_decode_against_both_oracles(idx.cpu().numpy(), out.cpu().numpy(), q, lab_o, K_o, V_o, ch, L, k,
+                                      "interleaved decode")
     # bad layout / range are refused before anything is enqueued
     with pytest.raises(ds.DsError) as e:
         ds.ds_append_kv(to_dev(K[:, :, :2]), to_dev(V[:, :, :2]), K_d, V_d, ch_d, lab_d, shp, L_max - 1, 2)

@@ -507,3 +507,27 @@ def test_workload_generator_is_seeded_and_has_static_outliers():
         assert (std[rest] < 1.5).all()
     assert WORKLOADS["C3"].algorithmic_bytes() == 100663296
     assert WORKLOADS["C2"].algorithmic_bytes() == 268435456
+
+
+def test_pins_hold_under_sanitizers():
+    """The oracle built with -fsanitize=address,undefined passes every pin above in a process of
+    its own (the ASan runtime has to be preloaded into the interpreter), and neither sanitizer
+    reports anything: no read or write outside a buffer, no signed overflow, no misaligned access."""
+    import subprocess
+    import sys
+    if O.SANITIZE:
+        pytest.skip("already running on the sanitized build")
+    O.build(sanitize=True)
+    env = dict(os.environ)
+    env["DS_ORACLE_SANITIZE"] = "1"
+    env["LD_PRELOAD"] = ":".join(x for x in (O.asan_runtime(), env.get("LD_PRELOAD", "")) if x)
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=0:verify_asan_link_order=0"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
+    env["OMP_NUM_THREADS"] = "4"
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-p", "no:cacheprovider"],
+                         env=env, capture_output=True, text=True, timeout=900,
+                         cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    tail = (res.stdout + res.stderr)[-3000:]
+    assert res.returncode == 0, tail
+    assert "AddressSanitizer" not in res.stdout + res.stderr and "runtime error" not in res.stdout + res.stderr, tail
+    assert " passed" in res.stdout, tail

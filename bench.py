@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3", help="C1, C2, C3 (headline), C4a, C4b; C5 = offload pipeline")
+    ap.add_argument("--shape", default="",
+                    help="B,Hq,Hkv,L,r,k: the named workload with these sizes instead (studies of one part of the path: "
+                         "a single unit, almost no rows); d = 128")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer caches to rotate over (0 = workload's)")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-dense", action="store_true")
@@ -85,6 +88,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = WORKLOADS[args.workload]
+    if args.shape:
+        B_, Hq_, Hkv_, L_, r_, k_ = (int(x) for x in args.shape.split(","))
+        w = w.scaled(name=f"{w.name} as {args.shape}", B=B_, Hq=Hq_, Hkv=Hkv_, L=L_, r=r_, k=k_,
+                     note=f"custom shape B{B_} Hq{Hq_} Hkv{Hkv_} L{L_} r{r_} k{k_}")
     for kv in filter(None, args.tune.split(",")):
         kn, val = kv.split("=")
         ds.ds_tune_set(int(kn), int(val))

@@ -47,6 +47,16 @@ __device__ __forceinline__ bool is_selected(uint32_t key, int t, uint32_t T, int
     return key > T || (key == T && t <= tcut);
 }
 
+// In-launch hand-over.  These workspace arrays are written by one workgroup and read by another
+// inside the same launch: the unit histograms (`hist`, `coarse`), the candidate list (`cand`), the
+// per-chunk counts and offsets (`ndef`, `offs`), the attention partials (`part`) and the words of
+// the UnitCtl records.  Every such read goes through ld_dev and every such write through st_dev
+// or an agent-scope atomic -- never through a plain load, which could be served from a stale line
+// of the reader's L2 without any error and only now and then.  Plain stores to them are allowed
+// only for clearing what nobody reads again in this launch.  tests/test_abi_host.py greps the
+// kernels for reads that break the rule.  (The reason for not using fences instead is measured:
+// see below.)
+//
 // Data that one workgroup hands to another inside a kernel goes through these
 // device-scope accesses: the stores are written through to the device's
 // coherence point and the loads read it there, so no cache needs flushing.

@@ -178,3 +178,29 @@ def test_planner_follows_the_device_it_is_told_of():
     for bad in ((0, 8, 160 << 10), (100, 8, 160 << 10), (64, 8, 1024)):
         with pytest.raises(ds.DsError):
             ds.ds_pretend_device(*bad)
+
+
+def test_handed_over_arrays_are_never_read_with_plain_loads():
+    """Host only, a grep over the attention kernels: the workspace arrays that one workgroup
+    writes and another reads inside a launch (unit histograms, candidate list, per-chunk counts
+    and offsets, partials) may be read only through ld_dev (device-scope loads).  A plain
+    indexed read -- `x = cu[i]`, `... hu[i] + ...` -- could be served from a stale cache line.
+    Allowed forms: the address taken for an atomic (`&hu[i]`), a clearing store (`hu[i] = 0`)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    csrc = os.path.join(root, "paper_2408_07092_amd", "csrc")
+    names = r"(?:cu|hu|cuh|a\.cand|a\.ndef|a\.offs_rw|a\.part|a\.hist|a\.coarse|po|pg|part_unit|ph|pc)"
+    bad = []
+    for fn in ("ds_attend.hip", "ds_attend_core.h"):
+        for ln, line in enumerate(open(os.path.join(csrc, fn)), 1):
+            code = line.split("//")[0]
+            for m in re.finditer(r"(?<![\w.&])" + names + r"\s*\[", code):
+                rest = code[m.end():]
+                depth, i = 1, 0
+                while i < len(rest) and depth:
+                    depth += {"[": 1, "]": -1}.get(rest[i], 0)
+                    i += 1
+                after = rest[i:].lstrip()
+                if after.startswith("=") and not after.startswith("=="):
+                    continue                     # a store
+                bad.append(f"{fn}:{ln}: {line.strip()}")
+    assert not bad, "plain reads of in-launch hand-over arrays:\n" + "\n".join(bad)

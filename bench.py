@@ -22,20 +22,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
-def counted_traffic(workload, kernel):
+def counted_traffic(workload, kernel, library_version):
     """HBM bytes per launch of `kernel` on `workload` as counted by rocprofv3 (FETCH_SIZE plus
     WRITE_SIZE, each scaled by a plain kernel of known size): read from the committed counter
-    summary, None when that summary has no line for this kernel and workload."""
+    summary, which names the library version it was taken on.  None when that is not the
+    version loaded here (the kernels have changed since), or when the summary has no line for
+    this kernel and workload."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    found, version_ok = None, False
     try:
         with open(path) as f:
             for line in f:
                 tok = line.split()
+                if len(tok) == 2 and tok[0] == "library_version":
+                    version_ok = int(tok[1]) == library_version
                 if len(tok) >= 4 and tok[0] == "traffic_bytes_per_launch" and tok[1] == workload and tok[2] == kernel:
-                    return int(tok[3])
+                    found = int(tok[3])
     except OSError:
         pass
-    return None
+    return found if version_ok else None
 
 
 def parse():
@@ -231,7 +236,7 @@ def main():
                    "label_bits": args.label_bits},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None if (args.interleaved or args.label_bits == 4) else counted_traffic(w.name, dom),
+                     "traffic": None if (args.interleaved or args.label_bits == 4) else counted_traffic(w.name, dom, ds.ds_version()),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": dom_us},
     }
     extra = {

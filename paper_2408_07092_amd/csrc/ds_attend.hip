@@ -254,7 +254,9 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     // launch starts is not computed at all: its output is NaN again.
     __shared__ uint32_t s_failed;
     auto raise_err = [&](uint32_t code) {
-        st_dev(&ctl->err, code);
+        uint32_t none = 0u;  // (the unit's first code stays)
+        __hip_atomic_compare_exchange_strong(&ctl->err, &none, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
         s_failed = 1u;
     };
     auto poison_out = [&]() {
@@ -273,6 +275,16 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         if (refuse_if_poisoned()) return;
     }
 
+    // the group's query rows (up to eight at a time), loaded for the label query; single heads and
+    // pairs attend with them too, so that no load of q sits between the lists and the rows
+    __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[SMODE != 0 ? 8 : 1][kD];
+    if constexpr (SMODE == 0 && GT <= 2) {
+        if (tid < GT * 16) {
+            const int g = tid >> 4, p = tid & 15;
+            const _Float16 *q0 = a.q + ((size_t)b * a.Hq + (size_t)h * a.G) * kD;
+            *reinterpret_cast<uint4 *>(&qsh[g][p * 8]) = *reinterpret_cast<const uint4 *>(q0 + (size_t)g * kD + p * 8);
+        }
+    }
     uint32_t bstar = kHistBins - 1, krem_unit = 1;
     if constexpr (SMODE != 0) {
         // ---- 0. Algorithm 1 steps 1-2 right here: stream the chunk's label rows, keys go to LDS
@@ -288,7 +300,6 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             else return hist_own[i];
         };
         __shared__ float qs_sh[RR];
-        __shared__ __attribute__((aligned(16))) _Float16 qrow_sh[8][kD];
         if constexpr (kQ4) {
             // label query of the group times the step of each channel (amax / 7); zero beyond r
             int c_q = 0;
@@ -322,7 +333,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 uint4 cv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    cv[i] = *reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * WGT * TPL, t_lastq) * WW);
+                    cv[i] = stream_load(reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * WGT * TPL, t_lastq) * WW));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
@@ -354,7 +365,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             for (int i = 0; i < SD; ++i) {
                 const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * WGT, t1 - 1) * SMODE);
 #pragma unroll
-                for (int j = 0; j < NV; ++j) v[i][j] = row[j];
+                for (int j = 0; j < NV; ++j) v[i][j] = label_load<NV>(row + j);
             }
         };
         int c_q = 0;
@@ -966,19 +977,16 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             DS_TR(5);
             wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride, od);
         } else {
-            if (tid < GT * 16) {
-                const int g = tid >> 4, p = tid & 15;
-                *reinterpret_cast<uint4 *>(&qsh[g][p * 8]) = *reinterpret_cast<const uint4 *>(q0 + (size_t)g * kD + p * 8);
-            }
-            __syncthreads();
+            // (the query rows have been in LDS since the kernel's first steps, barriers passed)
+            const _Float16(*qrows)[kD] = SMODE != 0 ? qrow_sh : qsh;
             RowState<GT> st;
             st.init();
             DS_PRIO(0);
-            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_first, row_def, qsh, st);
+            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_first, row_def, qrows, st);
             DS_PRIO(3);
             if (g0 == 0) { DS_TR(3); settle(); }
             DS_PRIO(2);
-            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qsh, st);
+            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qrows, st);
             DS_PRIO(3);
             DS_TR(5);
             wg_store_partial<GT, NW>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);

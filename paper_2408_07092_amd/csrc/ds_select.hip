@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
             const int t = min(t0 + i * kWG, t_end - 1);
             const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)t * (NV * 8));
 #pragma unroll
-            for (int j = 0; j < NV; ++j) v[i][j] = row[j];
+            for (int j = 0; j < NV; ++j) v[i][j] = label_load<NV>(row + j);
         }
     };
     DS_TR(0);
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
                 uint4 cv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    cv[i] = *reinterpret_cast<const uint4 *>(cu + (size_t)min(t0 + i * kWG * TPL, t_lastq) * WW);
+                    cv[i] = stream_load(reinterpret_cast<const uint4 *>(cu + (size_t)min(t0 + i * kWG * TPL, t_lastq) * WW));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // Template: GT heads per pass (1, 2 on the vector ALUs; 4, 8, 16 on the matrix cores), SMODE see
 // 0./1., RPS rows per 16-lane slot in flight (4; 8 = the 1024-thread variant of one workgroup
 // per unit that has a CU to itself).
-template <int GT, int SMODE, int RPS = 4>
+template <int GT, int SMODE, int RPS = 4, bool ST = true>
 __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {
     // Workgroup size: 256 threads; 1024 (four wavefronts per SIMD, 128 registers each: RPS = 8)
@@ -333,7 +333,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 uint4 cv[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    cv[i] = stream_load(reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * WGT * TPL, t_lastq) * WW));
+                    cv[i] = stream_load<ST>(reinterpret_cast<const uint4 *>(codes + (size_t)min(tb + i * WGT * TPL, t_lastq) * WW));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t c4[4] = {cv[i].x, cv[i].y, cv[i].z, cv[i].w};
@@ -365,7 +365,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             for (int i = 0; i < SD; ++i) {
                 const half8 *row = reinterpret_cast<const half8 *>(lab + (size_t)min(tb + i * WGT, t1 - 1) * SMODE);
 #pragma unroll
-                for (int j = 0; j < NV; ++j) v[i][j] = label_load<NV>(row + j);
+                for (int j = 0; j < NV; ++j) v[i][j] = label_load<NV, ST>(row + j);
             }
         };
         int c_q = 0;
@@ -437,7 +437,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     #pragma unroll
                     for (int i = 0; i < kHistBins / WGT; ++i) {
                         cbin[i] = hist_at(tid + i * WGT);
-                        cc += hist_at(tid * 16 + i);
+                        cc += hist_at(tid * 16 + ((i + tid) & 15));  // (an order of its own per lane: see hist_select)
                     }
     #pragma unroll
                     for (int i = 0; i < kHistBins / WGT; ++i)
@@ -515,7 +515,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     #pragma unroll
                     for (int i = 0; i < kHistBins / WGT; ++i) {
                         cbin[i] = hist_at(tid + i * WGT);
-                        cc += hist_at(tid * 16 + i);
+                        cc += hist_at(tid * 16 + ((i + tid) & 15));  // (an order of its own per lane: see hist_select)
                     }
     #pragma unroll
                     for (int i = 0; i < kHistBins / WGT; ++i)
@@ -982,11 +982,11 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             RowState<GT> st;
             st.init();
             DS_PRIO(0);
-            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_first, row_def, qrows, st);
+            attend_rows<GT, RPS, NW, ST>(Ku, Vu, row_bytes, n_first, row_def, qrows, st);
             DS_PRIO(3);
             if (g0 == 0) { DS_TR(3); settle(); }
             DS_PRIO(2);
-            attend_rows<GT, RPS, NW>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qrows, st);
+            attend_rows<GT, RPS, NW, ST>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qrows, st);
             DS_PRIO(3);
             DS_TR(5);
             wg_store_partial<GT, NW>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
@@ -1099,23 +1099,34 @@ struct RaKernel {
 
 // smode: 0 = keys and threshold bin come from the scoring launch; 8 / 16 = fp16 labels of that
 // many channels scored here; -8 / -16 = 4-bit labels of up to that many channels scored here.
-template <int GT, int RPS>
+template <int GT, int RPS, bool ST = true>
 static RaFn ra_fn(int smode)
 {
     switch (smode) {
-    case 0: return RPS > 4 ? nullptr : static_cast<RaFn>(k_refine_attend<GT, 0, 4>);
-    case 8: return k_refine_attend<GT, 8, RPS>;
-    case 16: return k_refine_attend<GT, 16, RPS>;
-    case -8: return k_refine_attend<GT, -8, RPS>;
-    default: return k_refine_attend<GT, -16, RPS>;
+    case 0: return RPS > 4 ? nullptr : static_cast<RaFn>(k_refine_attend<GT, 0, 4, ST>);
+    case 8: return k_refine_attend<GT, 8, RPS, ST>;
+    case 16: return k_refine_attend<GT, 16, RPS, ST>;
+    case -8: return k_refine_attend<GT, -8, RPS, ST>;
+    default: return k_refine_attend<GT, -16, RPS, ST>;
     }
+}
+
+// Whether a sparse decode call marks its loads of label and K/V rows as streaming: when it moves
+// 16 MiB or more (the headline shape moves 96 MiB).  A call of a few MiB that finds its rows in the
+// caches is up to 1 us of 15 slower with the mark; single heads and pairs have a variant without.
+static bool streams_past_caches(const Plan &p, const ds_shape_t &s)
+{
+    const size_t per_unit = (size_t)s.L * s.r * 2 + (size_t)p.k_eff * 2 * kD * 2;
+    return (size_t)p.units * per_unit >= ((size_t)16 << 20);
 }
 
 static size_t ra_shmem(const Plan &p) { return (size_t)p.ch * 4 + (size_t)p.ch * 2 + (size_t)p.n_ch * 4; }
 
-static RaKernel ra_kernel(const Plan &p, int smode)
+static RaKernel ra_kernel(const Plan &p, const ds_shape_t &s, int smode)
 {
     const int gt = pick_gt(p.G);
+    if (gt <= 2 && !streams_past_caches(p, s) && !(smode && gt == 1 && ra_shmem(p) > (64u << 10) && p.n_ch == 1))
+        return {gt == 2 ? ra_fn<2, DS_MC_RPS, false>(smode) : ra_fn<1, DS_MC_RPS, false>(smode), 256};
     // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot in flight
     if (smode && gt == 1 && ra_shmem(p) > (64u << 10) && p.n_ch == 1) return {ra_fn<1, 8>(smode), 1024};
     switch (gt) {
@@ -1193,7 +1204,7 @@ bool refine_attend_fits(const Plan &p, const ds_shape_t &s, bool scores_itself, 
 {
     const int smode = ra_smode(s, scores_itself, q4);
     if (scores_itself && smode == 0) return false;
-    return ra_fits(ra_kernel(p, smode), p, smode);
+    return ra_fits(ra_kernel(p, s, smode), p, smode);
 }
 
 // score_label / score_channels: non-null to run the scoring in the same launch (fp16 labels of 8
@@ -1233,7 +1244,7 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     a.r = s.r;
     const int smode = ra_smode(s, score_label != nullptr, score_amax != nullptr);
     if (score_label && smode == 0) return hipErrorInvalidValue;
-    const RaKernel k = ra_kernel(p, smode);
+    const RaKernel k = ra_kernel(p, s, smode);
     if (!k.fn) return hipErrorInvalidValue;
     if (!ra_fits(k, p, smode)) return kNotResident;
     const dim3 grid(p.n_ch, p.units), block(k.threads);

@@ -69,16 +69,16 @@ struct RowState {
 #ifndef DS_ROWS_STREAM
 #define DS_ROWS_STREAM 1
 #endif
+template <bool ST = true>
 __device__ __forceinline__ half8 row_load(const half8 *p)
 {
 #if DS_ROWS_STREAM
-    return DS_STREAM_LOAD(p);
-#else
-    return *p;
+    if constexpr (ST) return DS_STREAM_LOAD(p);
 #endif
+    return *p;
 }
 
-template <int GT, int RPS = 4, int NW = 4, class RowOf>
+template <int GT, int RPS = 4, int NW = 4, bool ST = true, class RowOf>
 __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
                                             RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)
 {
@@ -99,8 +99,8 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
                 const uint32_t off = (uint32_t)row_of(min(rr + i * 4 + slot, n - 1)) * row_bytes + (uint32_t)part * 16u;
-                kr[i] = row_load(reinterpret_cast<const half8 *>(Ku + off));
-                vr[i] = row_load(reinterpret_cast<const half8 *>(Vu + off));
+                kr[i] = row_load<ST>(reinterpret_cast<const half8 *>(Ku + off));
+                vr[i] = row_load<ST>(reinterpret_cast<const half8 *>(Vu + off));
             }
         };
         auto fold = [&](half8 (&kr)[HB], half8 (&vr)[HB], int rr) {
@@ -160,8 +160,8 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
         }
 #pragma unroll
         for (int i = 0; i < RPS; ++i) {
-            kr[i] = row_load(reinterpret_cast<const half8 *>(Ku + off[i]));
-            vr[i] = row_load(reinterpret_cast<const half8 *>(Vu + off[i]));
+            kr[i] = row_load<ST>(reinterpret_cast<const half8 *>(Ku + off[i]));
+            vr[i] = row_load<ST>(reinterpret_cast<const half8 *>(Vu + off[i]));
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the arithmetic
 #pragma unroll

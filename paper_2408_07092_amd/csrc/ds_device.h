@@ -26,20 +26,23 @@ constexpr float kNegInf = -__builtin_inff();
 // wavefront's first load leaves every other 16 bytes of its lines for the second, which finds them
 // in the cache only if the first load was an ordinary one (measured on 16-channel labels:
 // streaming mark +3 us per layer).
-template <int NV>
+// ST = false: the variant for calls that move little data (no mark at all).
 #ifndef DS_LABEL_STREAM
 #define DS_LABEL_STREAM 1
 #endif
+template <int NV, bool ST = true>
 __device__ __forceinline__ half8 label_load(const half8 *p)
 {
 #if DS_LABEL_STREAM
-    if constexpr (NV == 1) return DS_STREAM_LOAD(p);
+    if constexpr (NV == 1 && ST) return DS_STREAM_LOAD(p);
 #endif
     return *p;
 }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <bool ST = true>
 __device__ __forceinline__ uint4 stream_load(const uint4 *p)
 {
+    if constexpr (!ST) return *p;
     const u32x4 v = DS_STREAM_LOAD(reinterpret_cast<const u32x4 *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
@@ -242,24 +245,26 @@ __device__ __forceinline__ void hist_select(Get get, uint32_t kth, uint32_t *s_w
         res[0] = 0u;
         res[1] = 1u;
     }
-    uint32_t loc[PER];
+    // A thread owns PER consecutive bins.  Their sum is taken in an order that starts at a
+    // different bin in every lane: read in the same order, the lanes of a wavefront would sit
+    // PER words apart -- on 32 / PER LDS banks, each read served in PER turns.
+    auto bin_at = [&](int i) { return FROM_TOP ? (NB - 1 - (tid * PER + i)) : tid * PER + i; };
     uint32_t sum = 0;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-        const int pos = tid * PER + i;
-        loc[i] = get(FROM_TOP ? (NB - 1 - pos) : pos);
-        sum += loc[i];
-    }
+    for (int i = 0; i < PER; ++i) sum += get(bin_at(PER > 1 ? ((i + tid) % PER) : i));
     uint32_t total;
     uint32_t before = block_exclusive_scan<NW>(sum, s_w, &total);
+    // (one thread at most: it reads its bins once more, all at once, and walks them in order)
     if (before < kth && before + sum >= kth) {
+        uint32_t loc[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) loc[i] = PER > 1 ? get(bin_at(i)) : sum;  // (a single bin may have come from memory)
         bool done = false;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             if (!done) {
                 if (before + loc[i] >= kth) {
-                    const int pos = tid * PER + i;
-                    res[0] = (uint32_t)(FROM_TOP ? (NB - 1 - pos) : pos);
+                    res[0] = (uint32_t)bin_at(i);
                     res[1] = kth - before;
                     done = true;
                 } else {

@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kWG) void k_score(const _Float16 *__restrict__ q,
 #pragma unroll
         for (int i = 0; i < kHistBins / kWG; ++i) {
             c[i] = lh[tid + i * kWG];
-            cc += lh[tid * 16 + i];
+            cc += lh[tid * 16 + ((i + tid) & 15)];  // (an order of its own per lane: see hist_select)
         }
 #pragma unroll
         for (int i = 0; i < kHistBins / kWG; ++i)

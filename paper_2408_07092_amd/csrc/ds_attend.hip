@@ -19,19 +19,12 @@
 
 #include "ds_attend_core.h"
 
-#ifndef DS_MC_RPS
-#define DS_MC_RPS 4
-#endif
-#ifndef DS_NO_PRIO
 #define DS_PRIO(x) __builtin_amdgcn_s_setprio(x)
-#else
-#define DS_PRIO(x) do { } while (0)
-#endif
-#ifndef DS_SC_DEPTH
-#define DS_SC_DEPTH 8
-#endif
 
 namespace ds {
+
+constexpr int kRowsPerSlot = 4;   // rows of a 16-lane slot in flight (2: -0.2 us on the 64K workload, 8: +0.5)
+constexpr int kScoreDepth = 8;    // label loads of a thread in flight (4: +1.1 us; 12, 16: no gain)
 
 DS_TRACE_BUFFER
 
@@ -203,7 +196,7 @@ __global__ __launch_bounds__(kWG, (GT == 1 ? 8 : 1)) void k_attend(AttendArgs a)
 // 0./1., RPS rows per 16-lane slot in flight (4; 8 = the 1024-thread variant of one workgroup
 // per unit that has a CU to itself).
 template <int GT, int SMODE, int RPS = 4, bool ST = true>
-__global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
+__global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : GT == 1 ? 4 : 3))) void k_refine_attend(AttendArgs a)
 {
     // Workgroup size: 256 threads; 1024 (four wavefronts per SIMD, 128 registers each: RPS = 8)
     // for the variant that has a CU to itself (RPS > 4: one workgroup per unit, launched with
@@ -357,7 +350,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         }
         if constexpr (!kQ4) {
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
-        constexpr int SD = DS_SC_DEPTH;
+        constexpr int SD = kScoreDepth;
         half8 v[SD][NV];
         // (rows past the end of the chunk re-read its last row; their scores are dropped)
         auto issue = [&](int tb) {
@@ -645,11 +638,13 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     }
     if constexpr (!kAllKeys) {
         if constexpr (SMODE == 0) __syncthreads();  // the keys were stored by other threads
-        // Each thread owns n_pass groups of four consecutive keys, one thread's after the other's,
-        // so that thread order is token order: one count, one scan over the workgroup, one pass
-        // that writes both lists in ascending token order.
+        // Each thread owns n_pass groups of four consecutive keys (group p of thread t: keys
+        // 4 (p WGT + t) ..: a wavefront's loads then cover the LDS banks evenly): one count, one
+        // scan over the workgroup, one pass that writes both lists, in thread order, which is the
+        // same on every run (only the index list has to be in token order, and that is written
+        // further down).
         auto block_keys = [&](int p, uint32_t (&k4)[4]) {
-            const int lt = (tid * n_pass + p) * 4;
+            const int lt = (p * WGT + tid) * 4;
             k4[0] = k4[1] = k4[2] = k4[3] = 0u;
             if (t0 + lt < t1) {
                 const uint4 v = *reinterpret_cast<const uint4 *>(keys_sh + lt);
@@ -673,9 +668,8 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             early_base = (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)(total >> 16), __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT);
         int dpos = (int)(ex & 0xffffu);
-        uint32_t cp = ex >> 16;
-        // candidates wait at the back of the row list, filled from its end (the front holds the
-        // definite rows; both together never exceed the chunk), until the unit-wide base is known
+        uint32_t cp = (total & 0xffffu) + (ex >> 16);
+        // the candidates follow the definite rows in the row list
         for (int p = 0; p < n_pass; ++p) {
             uint32_t k4[4];
             const int lt = block_keys(p, k4);
@@ -683,13 +677,16 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             for (int e = 0; e < 4; ++e) {
                 if (t0 + lt + e < t1 && k4[e] >= lo_key) {
                     if (k4[e] - lo_key >= (1u << kKeyShift)) sel[dpos++] = (uint16_t)(lt + e);
-                    else sel[a.ch - 1 - (int)(cp++)] = (uint16_t)(lt + e);
+                    else sel[cp++] = (uint16_t)(lt + e);
                 }
             }
         }
         n_def = (int)(total & 0xffffu);
         n_cand = total >> 16;
     }
+    // where the chunk's i-th candidate waits in the row list: behind the definite rows, or (the
+    // variant that looks at each key once) at the list's end, filled from the back
+    auto cand_slot = [&](uint32_t i) { return kAllKeys ? a.ch - 1 - (int)i : n_def + (int)i; };
     // A unit with this one workgroup keeps everything in LDS: no candidate list in memory, no
     // arrival, nothing to publish.
     const bool single = gridDim.x == 1;
@@ -709,7 +706,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         const uint32_t base = s_base;
         if (base + n_cand <= (uint32_t)a.L) {
             for (uint32_t i = tid; i < n_cand; i += WGT) {
-                const int lt = sel[a.ch - 1 - (int)i];
+                const int lt = sel[cand_slot(i)];
                 st_dev(cu + base + i, make_uint2(keys_sh[lt], (uint32_t)(t0 + lt)));
             }
         } else if (tid == 0) {
@@ -731,7 +728,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
         // staged token of this chunk
         auto cand_at = [&](uint32_t i) {
             if (single) {
-                const int lt = sel[a.ch - 1 - (int)i];
+                const int lt = sel[cand_slot(i)];
                 return make_uint2(keys_sh[lt], (uint32_t)(t0 + lt));
             }
             return ld_dev(cu + i);
@@ -858,7 +855,10 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
     // First the definite rows that fill whole rounds of the workgroup's wavefronts (64 rows a round,
     // or 4 * RPS per wavefront on the vector path); the rest of them joins the selected candidates in one list, so
     // that at most one round of the workgroup runs partly empty.
-    constexpr int kRound = (GT >= 4) ? 64 : 4 * NW * RPS;
+    // (the variants for calls that move little data run on a mostly idle device, where a round
+    //  trip is all that a round of rows costs: eight rows per slot in flight there)
+    constexpr int kRowsInFlight = ST ? RPS : 8;
+    constexpr int kRound = (GT >= 4) ? 64 : 4 * NW * kRowsInFlight;
     const int n_first = (n_def / kRound) * kRound;
     auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };
     auto row_rest = [&](int ri) { return t0 + (int)sel[n_first + ri]; };
@@ -908,18 +908,17 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 for (uint32_t m = msel[w]; m; m &= m - 1u) sel[cp++] = (uint16_t)key_slot(w * 32 + __builtin_ctz(m));
             n_sel = (int)total;
         }
-        // Without an index list to write, the chunk's candidates -- already listed, in token order,
-        // at the back of the row list -- are all there is to look at: one scan per 256 of them
-        // instead of one per 1024 keys.  (The selected ones are appended at the front; the two
-        // regions cannot meet as long as n_def + 2 n_cand <= ch.)
-        const bool from_list = !kAllKeys && !io && (uint32_t)n_def + 2u * n_cand <= (uint32_t)a.ch;
-        if (from_list) {
+        // The chunk's candidates -- already listed, behind the definite rows -- are all there is to
+        // look at for the row list: one scan per 256 of them.  The selected ones close up to the
+        // definite rows in place (a batch is read before it is written, and what it writes never
+        // reaches the next batch).
+        if constexpr (!kAllKeys) {
             for (uint32_t c0 = 0; c0 < n_cand; c0 += WGT) {
                 const uint32_t i = c0 + tid;
                 int lt = 0;
                 bool hit = false;
                 if (i < n_cand) {
-                    lt = sel[a.ch - 1 - (int)i];
+                    lt = sel[cand_slot(i)];
                     hit = is_selected(keys_sh[lt], t0 + lt, T, tcut);
                 }
                 uint32_t total;
@@ -928,32 +927,29 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
                 n_sel += (int)total;
             }
         }
-        for (int p = 0; p < (((kAllKeys && !io) || from_list) ? 0 : n_pass); ++p) {
+        // the chunk's slice of the index list, in token order: one scan per 1024 keys
+        for (int p = 0; p < (io ? n_pass : 0); ++p) {
             const int lt = (p * WGT + tid) * 4;
             uint32_t k4[4];
             own_keys(p, k4);
-            bool fs[4], fc[4];
-            uint32_t packed = 0;  // selected candidates | all selected << 16
+            bool fs[4];
+            uint32_t mine = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 fs[e] = (t0 + lt + e < t1) && is_selected(k4[e], t0 + lt + e, T, tcut);
-                fc[e] = fs[e] && (k4[e] - lo_key < (1u << kKeyShift));
-                packed += (fc[e] ? 1u : 0u) + (fs[e] ? 0x10000u : 0u);
+                mine += fs[e] ? 1u : 0u;
             }
             uint32_t total;
-            const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
-            int cp = n_def + n_sel + (int)(ex & 0xffffu);
-            uint32_t ap = off + (uint32_t)all_base + (ex >> 16);
+            const uint32_t ex = block_exclusive_scan<NW>(mine, s_w, &total);
+            uint32_t ap = off + (uint32_t)all_base + ex;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (!kAllKeys && fc[e]) sel[cp++] = (uint16_t)(lt + e);
-                if (io && fs[e]) {
+                if (fs[e]) {
                     if (ap < (uint32_t)a.k_eff) io[ap] = t0 + lt + e;
                     ++ap;
                 }
             }
-            if (!kAllKeys) n_sel += (int)(total & 0xffffu);
-            all_base += (int)(total >> 16);
+            all_base += (int)total;
         }
         if (io && c == 0)
             for (int i = a.k_eff + tid; i < a.k; i += WGT) io[i] = -1;
@@ -982,11 +978,11 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (GT == 1 ? 4
             RowState<GT> st;
             st.init();
             DS_PRIO(0);
-            attend_rows<GT, RPS, NW, ST>(Ku, Vu, row_bytes, n_first, row_def, qrows, st);
+            attend_rows<GT, kRowsInFlight, NW, ST>(Ku, Vu, row_bytes, n_first, row_def, qrows, st);
             DS_PRIO(3);
             if (g0 == 0) { DS_TR(3); settle(); }
             DS_PRIO(2);
-            attend_rows<GT, RPS, NW, ST>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qrows, st);
+            attend_rows<GT, kRowsInFlight, NW, ST>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qrows, st);
             DS_PRIO(3);
             DS_TR(5);
             wg_store_partial<GT, NW>(st, wpart, po, (size_t)a.n_ch * kPartStride, od);
@@ -1126,15 +1122,15 @@ static RaKernel ra_kernel(const Plan &p, const ds_shape_t &s, int smode)
 {
     const int gt = pick_gt(p.G);
     if (gt <= 2 && !streams_past_caches(p, s) && !(smode && gt == 1 && ra_shmem(p) > (64u << 10) && p.n_ch == 1))
-        return {gt == 2 ? ra_fn<2, DS_MC_RPS, false>(smode) : ra_fn<1, DS_MC_RPS, false>(smode), 256};
+        return {gt == 2 ? ra_fn<2, kRowsPerSlot, false>(smode) : ra_fn<1, kRowsPerSlot, false>(smode), 256};
     // one workgroup per unit that has a CU to itself (LDS): 1024 threads, eight rows per slot in flight
     if (smode && gt == 1 && ra_shmem(p) > (64u << 10) && p.n_ch == 1) return {ra_fn<1, 8>(smode), 1024};
     switch (gt) {
-    case 16: return {ra_fn<16, DS_MC_RPS>(smode), 256};
-    case 8: return {ra_fn<8, DS_MC_RPS>(smode), 256};
-    case 4: return {ra_fn<4, DS_MC_RPS>(smode), 256};
-    case 2: return {ra_fn<2, DS_MC_RPS>(smode), 256};
-    default: return {ra_fn<1, DS_MC_RPS>(smode), 256};
+    case 16: return {ra_fn<16, kRowsPerSlot>(smode), 256};
+    case 8: return {ra_fn<8, kRowsPerSlot>(smode), 256};
+    case 4: return {ra_fn<4, kRowsPerSlot>(smode), 256};
+    case 2: return {ra_fn<2, kRowsPerSlot>(smode), 256};
+    default: return {ra_fn<1, kRowsPerSlot>(smode), 256};
     }
 }
 

@@ -58,26 +58,21 @@ struct RowState {
     }
 };
 
+// A 16-byte piece of a K or V row: read once per call, gathered or front to back, so the load is
+// marked as streaming (measured: dense decode 191 -> 176 us on the 64K workload, the gathers of the
+// sparse path 0.7 to 2.5 us per layer).
+template <bool ST = true>
+__device__ __forceinline__ half8 row_load(const half8 *p)
+{
+    if constexpr (ST) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
 // The calling wavefront's share of the workgroup's n rows: with RPS rows per 16-lane slot in
 // flight, rows wave*4*RPS + NW*4*RPS*i ..  (NW wavefronts; RPS = 4: 64 rows of a 256-thread
 // workgroup per round trip and 8 loads per lane; larger RPS for a workgroup that has a CU to itself).
 // row_of(ri) gives the row number of list entry ri; a row's K (V) bytes start at
 // Ku (Vu) + row * row_bytes.  qsh holds the GT query rows in LDS.
-// A 16-byte piece of a K or V row: read once per call, gathered or front to back, so the load is
-// marked as streaming (measured: dense decode 191 -> 176 us on the 64K workload, the gathers of the
-// sparse path 0.7 to 2.5 us per layer).
-#ifndef DS_ROWS_STREAM
-#define DS_ROWS_STREAM 1
-#endif
-template <bool ST = true>
-__device__ __forceinline__ half8 row_load(const half8 *p)
-{
-#if DS_ROWS_STREAM
-    if constexpr (ST) return DS_STREAM_LOAD(p);
-#endif
-    return *p;
-}
-
 template <int GT, int RPS = 4, int NW = 4, bool ST = true, class RowOf>
 __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint32_t row_bytes, int n,
                                             RowOf row_of, const _Float16 (*qsh)[kD], RowState<GT> &st)

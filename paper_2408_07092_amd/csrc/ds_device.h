@@ -14,36 +14,26 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_inff();
 
-// Loads of data that is read once per call (label rows, K/V rows): marked non-temporal, which
-// streams them past the caches' replacement (measured on this part: 6.3 -> 7.0 TB/s on a 1 GiB
-// read).  -DDS_PLAIN_LOADS turns the mark off.
-#ifndef DS_PLAIN_LOADS
-#define DS_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
-#else
-#define DS_STREAM_LOAD(ptr) (*(ptr))
-#endif
+// Loads of data that is read once per call (label rows, K/V rows) are marked non-temporal, which
+// streams them past the caches' replacement (measured on this part: dense decode over 1 GiB 191 ->
+// 176 us).  ST = false: the variants for calls that move only a few MiB, which do better without.
+//
 // A 16-byte piece of a label row of NV pieces.  Rows of one piece stream; of rows of two pieces a
 // wavefront's first load leaves every other 16 bytes of its lines for the second, which finds them
 // in the cache only if the first load was an ordinary one (measured on 16-channel labels:
 // streaming mark +3 us per layer).
-// ST = false: the variant for calls that move little data (no mark at all).
-#ifndef DS_LABEL_STREAM
-#define DS_LABEL_STREAM 1
-#endif
 template <int NV, bool ST = true>
 __device__ __forceinline__ half8 label_load(const half8 *p)
 {
-#if DS_LABEL_STREAM
-    if constexpr (NV == 1 && ST) return DS_STREAM_LOAD(p);
-#endif
-    return *p;
+    if constexpr (NV == 1 && ST) return __builtin_nontemporal_load(p);
+    else return *p;
 }
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <bool ST = true>
 __device__ __forceinline__ uint4 stream_load(const uint4 *p)
 {
     if constexpr (!ST) return *p;
-    const u32x4 v = DS_STREAM_LOAD(reinterpret_cast<const u32x4 *>(p));
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 

@@ -314,7 +314,8 @@ def main():
 # Stage numbers that thread 0 of every workgroup of the attention launch stamps (DS_TR in
 # csrc/ds_attend.hip), in the order a workgroup passes them.
 TRACE_STAGES = [(0, "start"), (11, "chunk scored (keys in LDS)"), (12, "unit histogram complete"),
-                (10, "threshold bin known"), (1, "lists made, candidates handed over"), (2, "arrived at unit counter"),
+                (10, "threshold bin known"), (13, "keys counted against the bin"),
+                (1, "lists made, candidates handed over"), (2, "arrived at unit counter"),
                 (8, "refiner: candidate loads issued"),
                 (14, "refiner: first radix pass done"), (15, "refiner: exact threshold known"),
                 (9, "refiner: published, histograms cleared"),

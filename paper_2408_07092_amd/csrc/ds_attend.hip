@@ -350,7 +350,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
         }
         if constexpr (!kQ4) {
         const _Float16 *lab = a.label + (size_t)u * a.L_max * SMODE;
-        constexpr int SD = kScoreDepth;
+        constexpr int SD = ST ? kScoreDepth : 2 * kScoreDepth;  // (a mostly idle device: fewer round trips)
         half8 v[SD][NV];
         // (rows past the end of the chunk re-read its last row; their scores are dropped)
         auto issue = [&](int tb) {
@@ -652,22 +652,26 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             }
             return lt;
         };
+        // (no branches per key: which list a key goes to is arithmetic, its store is predicated)
         uint32_t packed = 0;  // definite count | candidate count << 16
         for (int p = 0; p < n_pass; ++p) {
             uint32_t k4[4];
             const int lt = block_keys(p, k4);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (t0 + lt + e < t1 && k4[e] >= lo_key)
-                    packed += (k4[e] - lo_key < (1u << kKeyShift)) ? 0x10000u : 1u;
+            for (int e = 0; e < 4; ++e) {
+                const bool in = t0 + lt + e < t1 && k4[e] >= lo_key;
+                const bool cand = k4[e] - lo_key < (1u << kKeyShift);
+                packed += in ? (cand ? 0x10000u : 1u) : 0u;
+            }
         }
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
+        DS_TR(13);
         // the chunk's place in the unit's candidate list is fetched while the lists are written
         if (gridDim.x != 1 && tid == 0 && (total >> 16))
             early_base = (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)(total >> 16), __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT);
-        int dpos = (int)(ex & 0xffffu);
+        uint32_t dpos = ex & 0xffffu;
         uint32_t cp = (total & 0xffffu) + (ex >> 16);
         // the candidates follow the definite rows in the row list
         for (int p = 0; p < n_pass; ++p) {
@@ -675,10 +679,11 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             const int lt = block_keys(p, k4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (t0 + lt + e < t1 && k4[e] >= lo_key) {
-                    if (k4[e] - lo_key >= (1u << kKeyShift)) sel[dpos++] = (uint16_t)(lt + e);
-                    else sel[cp++] = (uint16_t)(lt + e);
-                }
+                const bool in = t0 + lt + e < t1 && k4[e] >= lo_key;
+                const bool cand = k4[e] - lo_key < (1u << kKeyShift);
+                if (in) sel[cand ? cp : dpos] = (uint16_t)(lt + e);
+                cp += (in && cand) ? 1u : 0u;
+                dpos += (in && !cand) ? 1u : 0u;
             }
         }
         n_def = (int)(total & 0xffffu);
@@ -750,15 +755,52 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
         if (tid == 0) s_cnt2 = 0u;  // (pass 1 has barriers before its first use)
         DS_TR(8);
         uint32_t krem = krem_unit;
-        svc_radix_pass<1024 / WGT, true, NW>(each, [](uint2) { return true; },
-                                [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
-        const uint32_t pre22 = (bstar << 10) | s_res[0];
-        krem = s_res[1];
-        const uint32_t n22 = lh[s_res[0]];  // candidates that share the k-th key's 22-bit prefix
-        __syncthreads();
-        DS_TR(14);
         bool settled = false;
-        if (n22 <= 64u) {
+        // Up to 256 candidates (short units, as a rule): one per thread, each counts the candidates
+        // that sort before it -- key descending, token ascending -- out of LDS, sixteen per step;
+        // the one with krem - 1 before it is the unit's k-th key, and its token is the tie cut.
+        constexpr uint32_t kRankAll = 256;
+        if (n >= 1u && n <= kRankAll) {
+            // (key and inverted token as one 64-bit number: sorts before <=> larger; 0 for the rest)
+            unsigned long long *s_c = reinterpret_cast<unsigned long long *>(lh);  // (2 KiB of the radix bins' 4)
+            const uint2 me2 = ce[0];
+            const unsigned long long me =
+                (uint32_t)tid < n ? ((unsigned long long)me2.x << 32) | (unsigned long long)(0xffffffffu - me2.y) : 0ull;
+            if (tid < (int)kRankAll) s_c[tid] = me;
+            __syncthreads();
+            if ((uint32_t)tid < n) {
+                uint32_t before = 0;
+                for (uint32_t j = 0; j < n; j += 16) {
+                    unsigned long long o[16];
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) o[e] = s_c[j + e];
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) before += o[e] > me ? 1u : 0u;
+                }
+                if (before + 1u == krem) {
+                    s_T[0] = me2.x;
+                    s_T[1] = me2.y;
+                }
+            }
+            __syncthreads();
+            // (a rank beyond the list means a workspace that was not cleared: take the long way)
+            if (krem >= 1u && krem <= n) {
+                T = s_T[0];
+                tcut = (int)s_T[1];
+                settled = true;
+            }
+        }
+        uint32_t pre22 = 0, n22 = 0xffffffffu;
+        if (!settled) {
+            svc_radix_pass<1024 / WGT, true, NW>(each, [](uint2) { return true; },
+                                    [](uint2 e) { return (e.x >> 10) & 1023u; }, krem, lh, s_w, s_res);
+            pre22 = (bstar << 10) | s_res[0];
+            krem = s_res[1];
+            n22 = lh[s_res[0]];  // candidates that share the k-th key's 22-bit prefix
+            __syncthreads();
+        }
+        DS_TR(14);
+        if (!settled && n22 <= 64u) {
             // One or two candidates as a rule: they are ranked among themselves by one wavefront,
             // in the order (key descending, token ascending); the one of rank krem is the unit's
             // k-th key, and its token is the tie cut.

@@ -201,6 +201,31 @@ def test_negative_zero_ties_with_positive_zero():
     full_parity(case, check_dense=False, what="signed zeros")
 
 
+def test_a_few_hundred_tied_candidates_are_ranked_by_token(decode_path):
+    """Up to 256 keys in the threshold bin take the direct ranking (one candidate per thread): with
+    200 equal scores at the threshold and room for 37 of them, the 37 lowest tokens must win; with
+    two distinct scores inside one bin, the higher one first."""
+    L, k = 3000, 37
+    q = np.zeros((1, 1, 128), np.float16); q[0, 0, 5] = 1.0
+    K = np.zeros((1, 1, L, 128), np.float16)
+    K[0, 0, :, 5] = -1.0
+    tied = np.arange(100, 2100, 10)                          # 200 tokens, spread over the chunks
+    K[0, 0, tied, 5] = 1.0
+    V = np.random.default_rng(3).standard_normal((1, 1, L, 128)).astype(np.float16)
+    ch = np.array([[5, 6, 7, 8, 9, 10, 11, 12]], np.int32)
+    case = Case(q, K, V, ch, L, k)
+    case.gpu_build_label()
+    _, idx = case.gpu_sparse()
+    assert idx[0, 0].tolist() == tied[:37].tolist()
+    full_parity(case, check_dense=False, what="200 ties")
+    K[0, 0, tied[50:90], 5] = 1.0009765625                   # same bin (the next binary16), 40 higher keys
+    case = Case(q, K, V, ch, L, 60)
+    case.gpu_build_label()
+    _, idx = case.gpu_sparse()
+    assert idx[0, 0].tolist() == sorted(tied[50:90].tolist() + tied[:20].tolist())
+    full_parity(case, check_dense=False, what="two keys in one bin")
+
+
 # ---------------------------------------------------------------- label cache
 def test_append_label_equals_build_and_error_codes():
     w = small_workload(2, 4, 4, 500, 8, 10)

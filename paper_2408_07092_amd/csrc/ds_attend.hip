@@ -219,10 +219,6 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
     // the launch that scores as well lives there too (it is dead before any of the above), with
     // the array padded to its 16 KiB where four heads make it smaller.
     constexpr bool kAliasHist = SMODE != 0 && GT >= 4;
-    // how a unit's workgroups learn the threshold bin when they score themselves: each finds it
-    // (vector variants), or the last to arrive finds and publishes it (matrix-core variants, where
-    // the former measured slower)
-    constexpr bool kAllFind = GT <= 2;
     constexpr int kWpartRows = (kAliasHist && 4 * GT * kPartStride < kHistBins) ? 8 : NW;
     __shared__ __attribute__((aligned(16))) float wpart[kWpartRows][GT][kPartStride];
     __shared__ __attribute__((aligned(16))) float red_own[GT >= 2 ? 1 : 8][kD];
@@ -415,14 +411,15 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             krem_unit = s_res[1];
             __syncthreads();
         } else if constexpr (NW == 4) {
-            if constexpr (kAllFind) {
+            {
                 // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
                 // memory (as in k_score).  Every workgroup then waits until all of the unit's have
                 // arrived and finds the threshold bin itself, with one round of loads: the 256 coarse
                 // bins, and with them the fine bins of the three coarse bins around the one that its
                 // own histogram points to (another round only if the unit's lies elsewhere).  Nobody
-                // has to publish anything; the histograms are cleared later, by the workgroup that
-                // settles the exact threshold, when every workgroup has long read them.
+                // has to publish anything; the histograms are cleared at the launch's end, by the
+                // workgroup that merges the unit, when every workgroup has long read them.  (The last
+                // to arrive finding the bin and publishing it measured the same or slower.)
                 uint32_t *hu = a.hist + (size_t)u * kHistBins;
                 uint32_t *cuh = a.coarse + (size_t)u * 256;
                 {
@@ -495,64 +492,6 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
                 } else if (tid == 0) {
                     s_T[0] = (uint32_t)(kHistBins - 1);
                     s_T[1] = 1u;
-                }
-            } else {
-                // Several workgroups per unit: the chunk histograms meet in the unit's histograms in
-                // memory (as in k_score); the last workgroup to arrive finds the threshold bin, clears
-                // the histograms and publishes (b*, rank, ready) as one word that the others wait for.
-                uint32_t *hu = a.hist + (size_t)u * kHistBins;
-                uint32_t *cuh = a.coarse + (size_t)u * 256;
-                uint2 *bready = reinterpret_cast<uint2 *>(&ctl->pad[0]);  // {b*, rank | 1<<31}
-                {
-                    uint32_t cbin[kHistBins / WGT], cc = 0;
-    #pragma unroll
-                    for (int i = 0; i < kHistBins / WGT; ++i) {
-                        cbin[i] = hist_at(tid + i * WGT);
-                        cc += hist_at(tid * 16 + ((i + tid) & 15));  // (an order of its own per lane: see hist_select)
-                    }
-    #pragma unroll
-                    for (int i = 0; i < kHistBins / WGT; ++i)
-                        if (cbin[i]) atomicAdd(&hu[tid + i * WGT], cbin[i]);
-                    if (cc) atomicAdd(&cuh[tid], cc);
-                }
-                const bool last_a = last_arrival(&ctl->arrive_a, gridDim.x, &s_flag);
-                DS_TR(12);
-                if (last_a) {
-                    hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
-                    const uint32_t cb = s_res[0], rank = s_res[1];
-                    __shared__ uint32_t s_fine[16];
-                    if (tid < 16) s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);  // from the top fine bin down
-                    __syncthreads();
-                    if (tid == 0) {
-                        uint32_t before = 0, bin = 0, krem = 1;
-                        for (int i = 0; i < 16; ++i) {
-                            if (before + s_fine[i] >= rank) {
-                                bin = cb * 16 + 15 - i;
-                                krem = rank - before;
-                                break;
-                            }
-                            before += s_fine[i];
-                        }
-                        st_dev(bready, make_uint2(bin, krem | 0x80000000u));
-                        st_dev(&ctl->arrive_a, 0u);
-                        s_T[0] = bin;
-                        s_T[1] = krem;
-                        s_ok = 1u;
-                    }
-                    for (int i = tid; i < kHistBins; i += WGT) hu[i] = 0u;  // nobody touches them again in this launch
-                    cuh[tid] = 0u;
-                } else if (tid == 0) {
-                    uint2 w = make_uint2(0u, 0u);
-                    uint32_t ok = 0;
-                    for (uint32_t it = 0; it < a.spin_limit; ++it) {
-                        w = ld_dev(bready);
-                        if (w.y & 0x80000000u) { ok = 1u; break; }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                    s_T[0] = ok ? w.x : (uint32_t)(kHistBins - 1);
-                    s_T[1] = ok ? (w.y & 0x7fffffffu) : 1u;
-                    s_ok = ok;
-                    if (!ok) raise_err(9u);
                 }
             }
             __syncthreads();
@@ -882,10 +821,6 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             st_dev(ready, make_uint2(T, (uint32_t)tcut | 0x80000000u));
             __hip_atomic_store(cand_arrive, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if constexpr (SMODE != 0 && !kAllFind) {
-            // every workgroup of the unit has arrived, so all of them have read the threshold bin
-            if (!single && tid == 0) st_dev(reinterpret_cast<uint2 *>(&ctl->pad[0]), make_uint2(0u, 0u));
-        }
         DS_TR(9);
     }
 
@@ -1062,7 +997,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
                        a.out + (size_t)u * a.G * kD, red, red_ml, [](int, bool) {});
     }
     DS_TR(7);
-    if constexpr (SMODE != 0 && kAllFind && NW == 4) {
+    if constexpr (SMODE != 0 && NW == 4) {
         // every workgroup of the unit has long read the unit's histograms and passed their arrival
         // counter: clean for the next call (off everybody's path but the launch's very end)
         uint4 *hu = reinterpret_cast<uint4 *>(a.hist + (size_t)u * kHistBins);

@@ -19,23 +19,24 @@ constexpr int kKeyShift = 32 - kHistBits;
 constexpr int kPartStride = 132; // floats per attention partial: m, l, 2 pad, acc[128]
 constexpr int kMaxChunks = 8192; // chunk offsets of one unit must fit one workgroup's LDS
 
-// Per-unit selection state in the workspace (64 bytes).  The three arrival
-// counters and ncand are zero between calls: the workgroup that consumes one
-// resets it (see ds_workspace_init).
+// Per-unit selection state in the workspace (64 bytes).  Counters and hand-over words are zero
+// between calls: the workgroup that consumes one resets it (see ds_workspace_init); err stays.
 struct UnitCtl {
-    uint32_t bstar;     // first-level bin holding the k-th largest key
+    uint32_t bstar;     // first-level bin holding the k-th largest key (left by k_score / k_cand)
     uint32_t krem;      // how many keys of that bin are selected (>= 1)
-    uint32_t ncand;     // candidates appended so far (keys in bin bstar)
-    uint32_t T;         // exact k-th largest key
+    uint32_t ncand;     // k_cand: candidates appended so far (keys in bin bstar)
+    uint32_t T;         // k_cand / k_score's tail: exact k-th largest key
     int32_t tcut;       // keys equal to T are selected iff token <= tcut
-    uint32_t arrive_a;  // workgroups of the scoring kernel that finished this unit
-    uint32_t arrive_b;  // same, candidate kernel
-    uint32_t arrive_c;  // same, attention kernels
-    uint32_t cnt_a;     // single-launch path: chunks scored / candidates written / partials written
-    uint32_t cnt_b;
+    uint32_t arrive_a;  // workgroups that have added their chunk histogram to the unit's (k_score, or
+                        // k_refine_attend when it scores itself)
+    uint32_t arrive_b;  // workgroups of k_cand that finished this unit
+    uint32_t arrive_c;  // workgroups of an attention kernel whose partial is written (k_refine_attend:
+                        // the high half counts those whose wait for another workgroup ran out)
+    uint32_t cnt_a;     // k_refine_attend: the exact threshold as published by the workgroup that
+    uint32_t cnt_b;     //   settled it, one 64-bit word {T, tie cut | 1 << 31}
     uint32_t cnt_c;
-    uint32_t err;       // single-launch path: non-zero if a bounded wait gave up (stays set)
-    uint32_t pad[4];
+    uint32_t err;       // non-zero once a bounded wait between workgroups gave up (the first code stays)
+    uint32_t pad[4];    // pad[2..3]: k_refine_attend's 64-bit counter {candidates so far, arrivals << 32}
 };
 static_assert(sizeof(UnitCtl) == 64, "UnitCtl is one 64-byte record");
 
@@ -95,7 +96,7 @@ DeviceCaps device_caps();                  // of the current device (cached per 
 void device_caps_pretend(const DeviceCaps *caps);  // test hook: overrides device_caps() for this thread (nullptr: off)
 
 // What the plan is for: the split select call (and anything that runs the candidate launch), a
-// decode call, or a decode call whose single workgroup per unit may do the scoring itself.
+// decode call, or a decode call whose attention launch may do the scoring as well.
 enum PlanFor { PLAN_SELECT = 0, PLAN_DECODE = 1, PLAN_DECODE_SCORING = 2 };
 bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose = PLAN_SELECT);
 bool make_dense_plan(const ds_shape_t &s, int n_tokens, DensePlan *p);

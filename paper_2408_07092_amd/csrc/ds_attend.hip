@@ -434,7 +434,10 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
                         if (cbin[i]) atomicAdd(&hu[tid + i * WGT], cbin[i]);
                     if (cc) atomicAdd(&cuh[tid], cc);
                 }
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                // (No wait for the adds to be performed before the arrival: an arrival that overtakes
+                //  its workgroup's adds is caught by the reader, who checks that the coarse counts add
+                //  up to L and the fine counts of the unit's coarse bin to its count, and looks again
+                //  if they do not.  One round trip less on every workgroup's path.)
                 __syncthreads();
                 uint32_t seen = 0;
                 if (tid == 0)
@@ -464,30 +467,60 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
                 __syncthreads();
                 DS_TR(12);
                 if (s_ok) {
-                    __shared__ uint32_t s_fine[16];
-                    uint32_t fv = 0;
-                    if (tid < 48) fv = ld_dev(hu + cb0 * 16 + tid);
-                    hist_select<1, true>([&](int bin) { return ld_dev(cuh + bin); }, (uint32_t)a.k_eff, s_w, s_res);
-                    const uint32_t cb = s_res[0], rank = s_res[1];
-                    if (cb - cb0 < 3u) {
-                        if (tid < 48 && (uint32_t)(tid >> 4) == cb - cb0) s_fine[15 - (tid & 15)] = fv;
-                    } else if (tid < 16) {
-                        s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);
-                    }
-                    __syncthreads();
-                    if (tid == 0) {
-                        // (s_fine runs from the coarse bin's top fine bin down)
-                        uint32_t before = 0, bin = cb * 16, krem = 1;
-                        for (int i = 0; i < 16; ++i) {
-                            if (before + s_fine[i] >= rank) {
-                                bin = cb * 16 + 15 - i;
-                                krem = rank - before;
-                                break;
-                            }
-                            before += s_fine[i];
+                    __shared__ uint32_t s_fine[16], s_cbn, s_valid;
+                    for (uint32_t attempt = 0;; ++attempt) {
+                        uint32_t fv = 0;
+                        if (tid < 48) fv = ld_dev(hu + cb0 * 16 + tid);
+                        const uint32_t myc = ld_dev(cuh + 255 - tid);  // (thread = coarse bin, from the top)
+                        if (tid == 0) {
+                            s_res[0] = 0u;
+                            s_res[1] = 1u;
+                            s_cbn = 0xffffffffu;
                         }
-                        s_T[0] = bin;
-                        s_T[1] = krem;
+                        uint32_t tot;
+                        const uint32_t above = block_exclusive_scan<NW>(myc, s_w, &tot);
+                        if (above < (uint32_t)a.k_eff && above + myc >= (uint32_t)a.k_eff) {
+                            s_res[0] = 255u - (uint32_t)tid;
+                            s_res[1] = (uint32_t)a.k_eff - above;
+                            s_cbn = myc;
+                        }
+                        __syncthreads();
+                        const uint32_t cb = s_res[0], rank = s_res[1];
+                        if (cb - cb0 < 3u) {
+                            if (tid < 48 && (uint32_t)(tid >> 4) == cb - cb0) s_fine[15 - (tid & 15)] = fv;
+                        } else if (tid < 16) {
+                            s_fine[tid] = ld_dev(hu + cb * 16 + 15 - tid);
+                        }
+                        __syncthreads();
+                        if (tid == 0) {
+                            // (s_fine runs from the coarse bin's top fine bin down)
+                            uint32_t fsum = 0;
+                            for (int i = 0; i < 16; ++i) fsum += s_fine[i];
+                            const bool valid = tot == (uint32_t)a.L && fsum == s_cbn;
+                            uint32_t before = 0, bin = cb * 16, krem = 1;
+                            for (int i = 0; i < 16; ++i) {
+                                if (before + s_fine[i] >= rank) {
+                                    bin = cb * 16 + 15 - i;
+                                    krem = rank - before;
+                                    break;
+                                }
+                                before += s_fine[i];
+                            }
+                            s_T[0] = bin;
+                            s_T[1] = krem;
+                            s_valid = valid ? 1u : 0u;
+                            // (counts that never add up: a workspace that was not cleared, or adds that
+                            //  do not arrive)
+                            if (!valid && attempt + 1u >= a.spin_limit) {
+                                raise_err(9u);
+                                s_T[0] = (uint32_t)(kHistBins - 1);
+                                s_T[1] = 1u;
+                                s_valid = 2u;
+                            }
+                        }
+                        __syncthreads();
+                        if (s_valid) break;
+                        __builtin_amdgcn_s_sleep(8);
                     }
                 } else if (tid == 0) {
                     s_T[0] = (uint32_t)(kHistBins - 1);

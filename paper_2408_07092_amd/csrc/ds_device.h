@@ -123,6 +123,8 @@ __device__ __forceinline__ void st_dev(uint2 *p, uint2 v)
 // have been performed, the barrier collects the workgroup, then one thread
 // bumps the counter.  The counter must be 0 before the first arrival; the
 // workgroup that gets true resets it.
+// (Data whose reader can check its completeness itself -- the unit histograms of
+// k_refine_attend, by their sums -- is handed over without the wait.)
 __device__ __forceinline__ bool last_arrival(uint32_t *counter, uint32_t total, uint32_t *s_flag)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");

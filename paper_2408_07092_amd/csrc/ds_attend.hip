@@ -611,10 +611,9 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
     if constexpr (!kAllKeys) {
         if constexpr (SMODE == 0) __syncthreads();  // the keys were stored by other threads
         // Each thread owns n_pass groups of four consecutive keys (group p of thread t: keys
-        // 4 (p WGT + t) ..: a wavefront's loads then cover the LDS banks evenly): one count, one
-        // scan over the workgroup, one pass that writes both lists, in thread order, which is the
-        // same on every run (only the index list has to be in token order, and that is written
-        // further down).
+        // 4 (p WGT + t) ..: a wavefront's loads then cover the LDS banks evenly).  Both lists are
+        // written in thread order, which is the same on every run (only the index list has to be
+        // in token order, and that is written further down).
         auto block_keys = [&](int p, uint32_t (&k4)[4]) {
             const int lt = (p * WGT + tid) * 4;
             k4[0] = k4[1] = k4[2] = k4[3] = 0u;
@@ -624,8 +623,10 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             }
             return lt;
         };
-        // (no branches per key: which list a key goes to is arithmetic, its store is predicated)
-        uint32_t packed = 0;  // definite count | candidate count << 16
+        // One look at each key: which of the thread's keys (64 at most) are definite and which are
+        // candidates goes into two masks, and the writes walk the set bits, few as they are
+        // (against a counting pass and a writing pass over the keys: C3 -0.2, C4a -0.9 us/layer).
+        unsigned long long mdef = 0, mcd = 0;
         for (int p = 0; p < n_pass; ++p) {
             uint32_t k4[4];
             const int lt = block_keys(p, k4);
@@ -633,9 +634,11 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             for (int e = 0; e < 4; ++e) {
                 const bool in = t0 + lt + e < t1 && k4[e] >= lo_key;
                 const bool cand = k4[e] - lo_key < (1u << kKeyShift);
-                packed += in ? (cand ? 0x10000u : 1u) : 0u;
+                if (in && !cand) mdef |= 1ull << (4 * p + e);
+                if (in && cand) mcd |= 1ull << (4 * p + e);
             }
         }
+        const uint32_t packed = (uint32_t)__builtin_popcountll(mdef) | ((uint32_t)__builtin_popcountll(mcd) << 16);
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<NW>(packed, s_w, &total);
         DS_TR(13);
@@ -643,20 +646,16 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
         if (gridDim.x != 1 && tid == 0 && (total >> 16))
             early_base = (uint32_t)__hip_atomic_fetch_add(cand_arrive, (unsigned long long)(total >> 16), __ATOMIC_RELAXED,
                                                           __HIP_MEMORY_SCOPE_AGENT);
+        // the candidates follow the definite rows in the row list; both in the thread's key order
         uint32_t dpos = ex & 0xffffu;
         uint32_t cp = (total & 0xffffu) + (ex >> 16);
-        // the candidates follow the definite rows in the row list
-        for (int p = 0; p < n_pass; ++p) {
-            uint32_t k4[4];
-            const int lt = block_keys(p, k4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool in = t0 + lt + e < t1 && k4[e] >= lo_key;
-                const bool cand = k4[e] - lo_key < (1u << kKeyShift);
-                if (in) sel[cand ? cp : dpos] = (uint16_t)(lt + e);
-                cp += (in && cand) ? 1u : 0u;
-                dpos += (in && !cand) ? 1u : 0u;
-            }
+        for (unsigned long long m = mdef; m; m &= m - 1ull) {
+            const int j = __builtin_ctzll(m);
+            sel[dpos++] = (uint16_t)(((j >> 2) * WGT + tid) * 4 + (j & 3));
+        }
+        for (unsigned long long m = mcd; m; m &= m - 1ull) {
+            const int j = __builtin_ctzll(m);
+            sel[cp++] = (uint16_t)(((j >> 2) * WGT + tid) * 4 + (j & 3));
         }
         n_def = (int)(total & 0xffffu);
         n_cand = total >> 16;

@@ -24,6 +24,11 @@
 namespace ds {
 
 constexpr int kRowsPerSlot = 4;   // rows of a 16-lane slot in flight (2: -0.2 us on the 64K workload, 8: +0.5)
+// ... on the vector path of the 256-thread variants: five, i.e. rounds of 80 rows.  A chunk of the
+// 64K workload has 128 +- 11 selected rows; with rounds of 64 nearly half the workgroups run a
+// third, almost empty round (31.1 -> 30.9 us/layer; batch 4 x 16K tokens 30.9 -> 30.5; six rows
+// per slot: 31.4).
+constexpr int kRowsPerSlotVector = 5;
 constexpr int kScoreDepth = 8;    // label loads of a thread in flight (4: +1.1 us; 12, 16: no gain)
 
 DS_TRACE_BUFFER
@@ -866,7 +871,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
     // that at most one round of the workgroup runs partly empty.
     // (the variants for calls that move little data run on a mostly idle device, where a round
     //  trip is all that a round of rows costs: eight rows per slot in flight there)
-    constexpr int kRowsInFlight = ST ? RPS : 8;
+    constexpr int kRowsInFlight = !ST ? 8 : (RPS > 4 || GT > 2) ? RPS : kRowsPerSlotVector;
     constexpr int kRound = (GT >= 4) ? 64 : 4 * NW * kRowsInFlight;
     const int n_first = (n_def / kRound) * kRound;
     auto row_def = [&](int ri) { return t0 + (int)sel[ri]; };

@@ -10,6 +10,8 @@
 // bit-reproducible.
 #pragma once
 
+#include <type_traits>
+
 #include "ds_device.h"
 
 namespace ds {
@@ -79,7 +81,7 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane >> 4, part = lane & 15;
-    if constexpr (RPS > 4) {
+    if constexpr (NW > 4) {
         // A workgroup with a CU to itself has nobody else to cover its memory latency, so the
         // RPS rows of a slot travel in two halves, the loads of one
         // issued before the other is folded in.  Rows reach a slot's state in the same order and
@@ -162,11 +164,10 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
             const half8 qv = *reinterpret_cast<const half8 *>(&qsh[g][part * 8]);
-            // the rows of a slot are folded into its state four at a time (fewer when fewer are in
-            // flight), in row order
-            constexpr int FG = RPS < 4 ? RPS : 4;
-#pragma unroll
-            for (int i0 = 0; i0 < RPS; i0 += FG) {
+            // the rows of a slot are folded into its state four at a time (the last group may be
+            // smaller), in row order
+            auto fold_group = [&](auto i0c, auto fgc) {
+                constexpr int i0 = decltype(i0c)::value, FG = decltype(fgc)::value;
                 float s[FG];
                 float mx = kNegInf;
 #pragma unroll
@@ -192,7 +193,11 @@ __device__ __forceinline__ void attend_rows(const char *Ku, const char *Vu, uint
                             st.acc[g][j] = __builtin_fmaf(p, (float)vr[i0 + i][j], st.acc[g][j]);
                     }
                 }
-            }
+            };
+            if constexpr (RPS >= 4) fold_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+            if constexpr (RPS >= 8) fold_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+            if constexpr (RPS % 4 != 0)
+                fold_group(std::integral_constant<int, RPS / 4 * 4>{}, std::integral_constant<int, RPS % 4>{});
         }
     }
 }

@@ -395,11 +395,11 @@ __device__ __forceinline__ void attend_rows_mfma(const char *Ku, const char *Vu,
         // about 22 bits (the weights are scaled by kPScale beforehand, see above, so that lo stays a
         // normal fp16 number for every weight that matters).  16 short issues per tile against 32
         // long ones with weights and V widened to fp32 (measured: C4a 52.0 -> 49.5 us/layer).
-        half4v ph, pl;
+        half4v p_hi, p_lo;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            ph[r] = (_Float16)p[r];
-            pl[r] = (_Float16)(p[r] - (float)ph[r]);
+            p_hi[r] = (_Float16)p[r];
+            p_lo[r] = (_Float16)(p[r] - (float)p_hi[r]);
         }
         // (the eight high parts first, then the eight low parts: two issues in a row into the
         //  same accumulator would wait for each other)
@@ -407,9 +407,9 @@ __device__ __forceinline__ void attend_rows_mfma(const char *Ku, const char *Vu,
 #pragma unroll
         for (int e = 0; e < 8; ++e) vb[e] = (half4v){vr[0][e], vr[1][e], vr[2][e], vr[3][e]};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st.O[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(ph, vb[e], st.O[e], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) st.O[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_hi, vb[e], st.O[e], 0, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st.O[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(pl, vb[e], st.O[e], 0, 0, 0);
+        for (int e = 0; e < 8; ++e) st.O[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_lo, vb[e], st.O[e], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (more) issue_v(r0 + 64);
     }

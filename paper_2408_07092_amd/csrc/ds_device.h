@@ -21,7 +21,8 @@ constexpr float kNegInf = -__builtin_inff();
 // A 16-byte piece of a label row of NV pieces.  Rows of one piece stream; of rows of two pieces a
 // wavefront's first load leaves every other 16 bytes of its lines for the second, which finds them
 // in the cache only if the first load was an ordinary one (measured on 16-channel labels:
-// streaming mark +3 us per layer).
+// streaming mark +3 us per layer).  (k_refine_attend loads such rows as whole lines, two tokens'
+// halves per lane, and lets neighbouring lanes swap: see swap_pairs.)
 template <int NV, bool ST = true>
 __device__ __forceinline__ half8 label_load(const half8 *p)
 {
@@ -35,6 +36,16 @@ __device__ __forceinline__ uint4 stream_load(const uint4 *p)
     if constexpr (!ST) return *p;
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Neighbouring lanes (2j, 2j + 1) exchange a 16-byte piece.
+__device__ __forceinline__ half8 swap_pairs(half8 v)
+{
+    typedef int int4v __attribute__((ext_vector_type(4)));
+    int4v x = __builtin_bit_cast(int4v, v);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x[k] = __builtin_amdgcn_update_dpp(0, x[k], 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    return __builtin_bit_cast(half8, x);
 }
 
 // Development aid, compiled out unless the library is built with -DDS_TRACE:

@@ -1011,9 +1011,15 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
             load_q_mfma(q0, n_heads, qreg);
             MfmaState st;
             st.init();
+            // (row loops at the lowest priority, hand-over sections at the highest: a workgroup
+            //  that is still making its lists shares the compute unit with two that stream rows)
+            DS_PRIO(0);
             attend_rows_mfma<false>(Ku, Vu, row_bytes, n_first, row_def, qreg, st, sc_sh[tid >> 6]);
+            DS_PRIO(3);
             if (g0 == 0) { DS_TR(3); settle(); }
+            DS_PRIO(2);
             attend_rows_mfma<false>(Ku, Vu, row_bytes, n_def - n_first + n_sel, row_rest, qreg, st, sc_sh[tid >> 6]);
+            DS_PRIO(3);
             DS_TR(5);
             wg_store_partial_mfma<GT>(st, wpart, n_heads, po, (size_t)a.n_ch * kPartStride, od);
         } else {

@@ -157,8 +157,25 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
         // every workgroup resident at once (six per CU on the vector path, three on the matrix
         // cores) when chunks of up to 4096 / 6144 tokens allow it
         if (p->G <= 2) {
-            ch = 1024;
-            while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 6 * caps.cus) ch *= 2;
+            // A launch that scores as well needs its whole grid resident, and LDS decides how many
+            // workgroups a CU holds (6 bytes a token for keys and row list, about 26 KiB of fixed
+            // arrays): the largest number of chunks per unit that gives four, else three, two, one
+            // workgroup per CU.  (Fixed chunks of up to 4096 tokens left 128 units of 32K tokens
+            // with 1024 workgroups of which 768 fit: scoring became a launch of its own, 55 us per
+            // layer against 46.5 with four chunks of 8192 tokens in one launch.)
+            if (purpose == PLAN_DECODE_SCORING) {
+                for (int w = 4; w >= 1 && ch == 0; --w) {
+                    const int n = std::min((caps.cus * w) / p->units, kMaxChunks);
+                    if (n < 2) continue;
+                    const int c = std::max(1024, (((s.L + n - 1) / n) + 63) & ~63);
+                    const size_t lds = (size_t)c * 6 + (size_t)((s.L + c - 1) / c) * 4 + (26u << 10);
+                    if (c <= 16384 && lds * w <= (size_t)caps.lds_per_cu) ch = c;
+                }
+            }
+            if (ch == 0) {
+                ch = 1024;
+                while (ch < 4096 && (int64_t)p->units * ((s.L + ch - 1) / ch) > 6 * caps.cus) ch *= 2;
+            }
         } else {
             ch = 2048;
             while (ch < 6144 && ch < s.L && (int64_t)p->units * ((s.L + ch - 1) / ch) > 3 * caps.cus) ch += 256;

@@ -391,6 +391,22 @@ def test_full_configs_decode_in_one_launch_by_default(name, decode_path):
     assert _decode_launches(case) == {"k_refine_attend": 1}
 
 
+def test_many_single_head_units_of_32k_tokens_decode_in_one_launch(decode_path):
+    """128 single-head units of 32K tokens: four workgroups per unit with chunks of 8192 tokens is
+    what the device holds at once (LDS), so that scoring, selection and attention stay one launch;
+    parity of that launch at full size against the oracle."""
+    if decode_path != "auto":
+        pytest.skip("default launch shape only")
+    w = Workload("long_single_heads", 4, 32, 32, 128, 32768, 8, 2048, 1)
+    t = make_layer_torch(w, "cuda", layer=1)
+    case = Case.from_torch(t, outlier_channels(w.Hkv, w.d), w.L, w.k)
+    rep = full_parity(case, check_dense=False, what="128 units x 32K")
+    plan = ds.ds_plan_describe(case.shape, 0)
+    assert plan["workgroups_per_unit"] == 4 and plan["tokens_per_workgroup"] == 8192, plan
+    assert _decode_launches(case) == {"k_refine_attend": 1}
+    print("128 units x 32K", rep)
+
+
 def test_full_config_c2():
     _full_config("C2")
 

@@ -369,11 +369,13 @@ int ds_tune_get(int knob);
  * How ds_sparse_decode would be launched for a shape (diagnostics and tests; pure host work
  * apart from asking the runtime for the kernel's occupancy).  label_kind: 0 = fp16 label cache,
  * 1 = no label cache, 2 = 4-bit label cache.  out[0] = launches by the planner's own model of the
- * device (1: one launch that scores, selects and attends; 2: scoring, then selection behind the
- * attention; 3: scoring, candidates, attention); out[1] = launches once the occupancy that the
+ * device (with out[6] = 1: launches that score, select and attend, one as a rule, two to four
+ * of a share of the units each when the units do not fit the device at once; otherwise 2:
+ * scoring, then selection behind the attention; 3: scoring, candidates, attention); out[1] =
+ * launches once the occupancy that the
  * runtime reports for the kernels has been taken into account (-1 when no device is visible);
- * out[2] = tokens per workgroup, out[3] = workgroups per unit, out[4] = workgroups in the
- * attention launch, out[5] = compute units planned for, out[6] = 1 if the attention launch
+ * out[2] = tokens per workgroup, out[3] = workgroups per unit, out[4] = workgroups of the
+ * attention launches together, out[5] = compute units planned for, out[6] = 1 if the attention launch
  * scores as well, out[7] = query heads per KV head.
  * ds_pretend_device makes the calling thread's plans (and residency checks) assume a device of
  * `cus` compute units on `xccs` dies with `lds_per_cu` bytes of LDS each, instead of the current

@@ -135,6 +135,7 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
                                             (purpose == PLAN_DECODE_SCORING && s.L > (1 << 12)))));
     int ch = tune_get(1);
     p->group_scores_itself = false;
+    p->unit_groups = 1;
     if (ch == 0 && p->refine_attend && !one_wg_units && p->G > 2 && purpose == PLAN_DECODE_SCORING) {
         // Query groups: one launch that scores as well pays off when all of its workgroups are
         // resident at once (a workgroup waits for the others of its unit twice).  Most
@@ -163,13 +164,22 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
             // workgroup per CU.  (Fixed chunks of up to 4096 tokens left 128 units of 32K tokens
             // with 1024 workgroups of which 768 fit: scoring became a launch of its own, 55 us per
             // layer against 46.5 with four chunks of 8192 tokens in one launch.)
+            // Units that do not fit at once even so (256 units of 32K tokens) go in two to four
+            // launches of a share of the units each, every one of them resident at once (two
+            // launches of 128 units: 93 us per layer against 105 with scoring as a launch of its own).
             if (purpose == PLAN_DECODE_SCORING) {
-                for (int w = 4; w >= 1 && ch == 0; --w) {
-                    const int n = std::min((caps.cus * w) / p->units, kMaxChunks);
-                    if (n < 2) continue;
-                    const int c = std::max(1024, (((s.L + n - 1) / n) + 63) & ~63);
-                    const size_t lds = (size_t)c * 6 + (size_t)((s.L + c - 1) / c) * 4 + (26u << 10);
-                    if (c <= 16384 && lds * w <= (size_t)caps.lds_per_cu) ch = c;
+                for (int g = 1; g <= 4 && ch == 0; ++g) {
+                    const int units_g = (p->units + g - 1) / g;
+                    for (int w = 4; w >= 1 && ch == 0; --w) {
+                        const int n = std::min((caps.cus * w) / units_g, kMaxChunks);
+                        if (n < 2) continue;
+                        const int c = std::max(1024, (((s.L + n - 1) / n) + 63) & ~63);
+                        const size_t lds = (size_t)c * 6 + (size_t)((s.L + c - 1) / c) * 4 + (26u << 10);
+                        if (c <= 16384 && lds * w <= (size_t)caps.lds_per_cu) {
+                            ch = c;
+                            p->unit_groups = g;
+                        }
+                    }
                 }
             }
             if (ch == 0) {
@@ -515,7 +525,8 @@ static bool label_may_score(const ds_shape_t &s, ScoreSrcKind kind)
 static bool plan_scores_itself(const Plan &p, bool may_score)
 {
     return may_score && (p.n_ch == 1 || tune_get(4) == 2 ||
-                         (tune_get(4) == 0 && p.G <= 2 && (int64_t)p.units * p.n_ch <= 4 * (int64_t)p.cus) ||
+                         (tune_get(4) == 0 && p.G <= 2 &&
+                          (int64_t)((p.units + p.unit_groups - 1) / p.unit_groups) * p.n_ch <= 4 * (int64_t)p.cus) ||
                          (tune_get(4) == 0 && p.group_scores_itself));
 }
 
@@ -595,14 +606,14 @@ ds_status_t ds_plan_describe(const ds_shape_t *shape, int32_t label_kind, int32_
     if (!make_plan(*shape, &p, may_score ? PLAN_DECODE_SCORING : PLAN_DECODE)) return DS_ERR_UNSUPPORTED;
     const bool si = plan_scores_itself(p, may_score);
     const bool ra = p.refine_attend && refine_attend_ok(p, si);
-    const int planned = !ra ? 3 : si ? 1 : 2;
+    const int planned = !ra ? 3 : si ? p.unit_groups : 2;
     int actual = -1;
     int n_dev = 0;
     if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
         actual = 3;
         if (ra) {
             const bool q4 = kind == SRC_Q4;
-            if (si && refine_attend_fits(p, *shape, true, q4)) actual = 1;
+            if (si && refine_attend_fits(p, *shape, true, q4)) actual = p.unit_groups;
             else if (refine_attend_ok(p, false) && refine_attend_fits(p, *shape, false, q4)) actual = 2;
         }
     }

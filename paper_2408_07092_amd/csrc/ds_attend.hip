@@ -44,6 +44,7 @@ struct AttendArgs {
     UnitCtl *ctl_rw;
     int Hq, Hkv, G, L, L_max, key_stride, ch, n_ch, k, k_eff, n_rows;
     int kv_stride;       // halves from one token's K (V) row to the next: d, or 2d when K|V interleave
+    int unit0;           // k_refine_attend: first unit of this launch (a launch may take a share of the units)
     // k_refine_attend only
     uint2 *cand;         // [units][L] (key, token) of the keys in bin b*, unordered
     uint32_t *ndef;      // [units][n_ch] keys above bin b* per chunk
@@ -231,7 +232,7 @@ __global__ __launch_bounds__((RPS > 4 ? 1024 : 256), (RPS > 4 ? 1 : (!ST ? 2 : G
     uint32_t *lh = reinterpret_cast<uint32_t *>(&red[0][0]);  // 1024 radix bins
 
     const int tid = threadIdx.x;
-    const int u = blockIdx.y, c = blockIdx.x;
+    const int u = blockIdx.y + a.unit0, c = blockIdx.x;
     const int b = u / a.Hkv, h = u % a.Hkv;
     const int t0 = c * a.ch, t1 = min(a.L, t0 + a.ch);
     constexpr int kMaxPass = 8;                              // ch <= 8192
@@ -1241,7 +1242,7 @@ static bool ra_fits(const RaKernel &k, const Plan &p, int smode)
     const int per_cu = ra_workgroups_per_cu(k, ra_shmem(p), caps);
     if (per_cu < 1) return false;
     if (p.n_ch == 1) return true;
-    if (smode != 0) return (int64_t)p.n_ch * p.units <= (int64_t)per_cu * caps.cus;
+    if (smode != 0) return (int64_t)p.n_ch * ((p.units + p.unit_groups - 1) / p.unit_groups) <= (int64_t)per_cu * caps.cus;
     const int dies = std::max(1, caps.xccs);
     return (p.n_ch + dies - 1) / dies <= per_cu * std::max(1, caps.cus / dies);
 }
@@ -1293,12 +1294,22 @@ hipError_t launch_refine_attend(const void *q, const void *K, const void *V, voi
     const RaKernel k = ra_kernel(p, s, smode);
     if (!k.fn) return hipErrorInvalidValue;
     if (!ra_fits(k, p, smode)) return kNotResident;
-    const dim3 grid(p.n_ch, p.units), block(k.threads);
-    void *args[] = {&a};
-    hipEvent_t ev_a = nullptr, ev_b = nullptr;
-    if (prof_events(KID_REFINE_ATTEND, &ev_a, &ev_b))
-        return hipExtLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st, ev_a, ev_b, 0);
-    return hipLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st);
+    // (a launch that scores as well may take a share of the units at a time: see make_plan)
+    const int groups = smode != 0 ? std::max(1, p.unit_groups) : 1;
+    const int per_group = (p.units + groups - 1) / groups;
+    for (int u0 = 0; u0 < p.units; u0 += per_group) {
+        a.unit0 = u0;
+        const dim3 grid(p.n_ch, std::min(per_group, p.units - u0)), block(k.threads);
+        void *args[] = {&a};
+        hipEvent_t ev_a = nullptr, ev_b = nullptr;
+        hipError_t e;
+        if (prof_events(KID_REFINE_ATTEND, &ev_a, &ev_b))
+            e = hipExtLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st, ev_a, ev_b, 0);
+        else
+            e = hipLaunchKernel(reinterpret_cast<const void *>(k.fn), grid, block, args, ra_shmem(p), st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_attend_dense(const void *q, const void *K, const void *V, void *ws, float *out,

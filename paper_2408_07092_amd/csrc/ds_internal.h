@@ -68,6 +68,7 @@ struct Plan {
     int key_stride;      // uint32 keys per unit (L rounded up to 4)
     bool refine_attend;  // ds_sparse_decode as scoring + one refine-and-attend launch
     bool group_scores_itself;  // query groups of 3+ heads: chunks sized so that this launch can do the scoring too
+    int unit_groups;     // the attention launch that scores as well is enqueued this many times, a share of the units each
     size_t off_ctl, off_hist, off_coarse, off_keys, off_cand, off_ndef, off_offs, off_part;
     size_t total;
 };

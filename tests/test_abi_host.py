@@ -165,7 +165,10 @@ def test_planner_follows_the_device_it_is_told_of():
         assert big["launches_planned"] == 1 and big["scores_itself"] == 1, (name, big)
         per_cu = 4 if big["heads_per_kv_head"] <= 2 else 3
         assert big["workgroups"] <= per_cu * 256, (name, big)
-        assert small["launches_planned"] >= 2 and small["scores_itself"] == 0, (name, small)
+        # (either scoring becomes a launch of its own, or the units go in several launches of
+        #  which each fits the small device at once)
+        assert small["launches_planned"] >= 2, (name, small)
+        assert small["scores_itself"] == 0 or small["workgroups"] <= small["launches_planned"] * per_cu * 64, (name, small)
         assert ws_small > 0
     # one workgroup per unit waits for nobody: the same plan on any device
     c1 = ds.shape(1, 32, 32, 128, 4096, 4096, 8, 256)

@@ -222,6 +222,9 @@ def main():
     dom_bytes = w.units * w.k * w.d * 2 * 2                   # k full K and V rows per unit
     if dom == "k_refine_attend" and "k_score" not in kernels_us:
         dom_bytes = alg                                       # that launch scored the units itself
+    # (units that do not fit the device at once go in several launches per layer, a share each)
+    per_layer = max(1, round(prof[dom][1] / (args.steps * n_layers)))
+    dom_bytes //= per_layer
     dom_us = kernels_us[dom]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9
 

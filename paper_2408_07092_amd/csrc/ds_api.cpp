@@ -306,7 +306,7 @@ const char *ds_strerror(ds_status_t status)
     return "unknown status";
 }
 
-int ds_version(void) { return 108; }
+int ds_version(void) { return 109; }
 
 ds_status_t ds_calibrate_channels(const uint16_t *q_calib, const uint16_t *k_calib, int32_t N,
                                   int32_t Hq, int32_t Hkv, int32_t d, int32_t r,

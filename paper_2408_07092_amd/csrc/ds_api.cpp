@@ -140,13 +140,19 @@ bool make_plan(const ds_shape_t &s, Plan *p, PlanFor purpose)
         // Query groups: one launch that scores as well pays off when all of its workgroups are
         // resident at once (a workgroup waits for the others of its unit twice).  Most
         // workgroups per CU first: the largest number of chunks per unit that still fits.
-        for (int w = 3; w >= 1 && ch == 0; --w) {
-            const int n = std::min((caps.cus * w) / p->units, kMaxChunks);
-            if (n < 1) continue;
-            const int c = std::max(2048, (((s.L + n - 1) / n) + 63) & ~63);  // (no point in tiny chunks)
-            if (c <= 8192 && group_wgs_per_cu(p->G, c, (s.L + c - 1) / c, caps) >= w) {
-                ch = c;
-                p->group_scores_itself = true;
+        // (units that do not fit at once even with one workgroup per CU go in two to four launches
+        //  of a share of the units each)
+        for (int g = 1; g <= 4 && ch == 0; ++g) {
+            const int units_g = (p->units + g - 1) / g;
+            for (int w = 3; w >= 1 && ch == 0; --w) {
+                const int n = std::min((caps.cus * w) / units_g, kMaxChunks);
+                if (n < 1) continue;
+                const int c = std::max(2048, (((s.L + n - 1) / n) + 63) & ~63);  // (no point in tiny chunks)
+                if (c <= 8192 && group_wgs_per_cu(p->G, c, (s.L + c - 1) / c, caps) >= w) {
+                    ch = c;
+                    p->group_scores_itself = true;
+                    p->unit_groups = g;
+                }
             }
         }
     }
